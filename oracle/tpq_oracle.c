@@ -1,0 +1,383 @@
+/*
+ * tpq_oracle.c -- plain scalar CPU oracle for the low-bit tensor-parallel
+ * partial-sum codec (calibration, encode, decode-and-reduce).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the GPU
+ * library can be checked against something written straight from the paper.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.  It shares no code, header, table or helper with the HIP path.
+ *
+ * What is computed (all arithmetic IEEE-754 binary32, round-to-nearest-even,
+ * no fused contraction, denormals kept; bf16 = upper 16 bits of binary32,
+ * converted with round-to-nearest-even):
+ *
+ *   calibration (paper Sec. 3 "Calibration", Eq. (1) and (2); Sec. 3
+ *   "Selecting High Precision Features"):
+ *     per sequence, per device i, per feature j: column min and max over the
+ *     S rows; exponential moving average with constant gamma, the first
+ *     sequence initialising the state; symmetric range R = 2*max(-m, M);
+ *     aggregated range Rbar_j = sum over devices; the k features with the
+ *     largest Rbar are the ones kept in BF16.
+ *
+ *   encode (paper Sec. 2 compression function C^(i); Fig. 2; Sec. 3): the k
+ *     selected features of each row are copied verbatim as bf16; the other
+ *     r = E-k features, taken in ascending feature order ("compacted"), are
+ *     quantised to 4 bits.  The quantiser is the group-wise asymmetric one
+ *     the workload definition asks for: per row, per group of G consecutive
+ *     compacted features, zero = group minimum, scale = bf16((max-min)/15),
+ *     code = rint((x - zero) * (1/scale)) clamped to 0..15; two codes per
+ *     byte, low nibble first.
+ *
+ *   decode_reduce (paper Sec. 2 decompression D^(i) and the sum over
+ *     devices; Fig. 2 caption): every device's message is dequantised
+ *     (x = code*scale + zero, outliers as they are) and the N results are
+ *     added in ascending device order, either in fp32 (rounded to bf16 once
+ *     at the end, or left fp32) or literally in bf16 (every term and every
+ *     partial sum rounded to bf16).
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * (brute force over all 16 codes in float64, verbatim outliers, half-step
+ * error bound, closed-form bit counts, Irwin-Hall variance of the summed
+ * error, hand-worked EMA examples, numpy stable-sort top-k, plain-sum special
+ * case k = E).  Parity unpinned: the byte layout of the message (nibble
+ * order, pad nibble, section order) is not fixed by the paper; it is this
+ * build's own choice and is only checked against its written description.
+ *
+ * Layouts here are dense (no row padding):
+ *   outl  uint16 [T][k]          codes uint8 [T][ceil(r/2)]
+ *   scale uint16 [T][ceil(r/G)]  zero  uint16 [T][ceil(r/G)]
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_ERR_ARG (-1)
+
+/* ---- bf16 <-> binary32 ------------------------------------------------- */
+
+static float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* round-to-nearest-even on the 16 discarded bits; inputs are finite */
+static uint16_t f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+static uint16_t f32_bits_hi(float f) /* exact when f is a bf16 value */
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+static int set_threads(int threads)
+{
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    omp_set_num_threads(threads);
+    return threads;
+#else
+    (void)threads;
+    return 1;
+#endif
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_num_procs();
+#else
+    return 1;
+#endif
+}
+
+/* ---- calibration ------------------------------------------------------- */
+
+/*
+ * One sequence of one device (Eq. (1), (2)).  Y is bf16 [S][ldY] with E used
+ * columns; m and M are that device's fp32 [E] state.  first != 0 means this is
+ * the first sequence: the state is set to the column min / max.
+ */
+int orc_calibrate_update(const uint16_t *Y, int64_t S, int64_t ldY, int E,
+                         int first, float gamma, float *m, float *M)
+{
+    if (!Y || !m || !M || S < 1 || E < 1 || ldY < E) return ORC_ERR_ARG;
+    const float keep = 1.0f - gamma;
+    for (int j = 0; j < E; ++j) {
+        float cmin = bf16_to_f32(Y[j]);
+        float cmax = cmin;
+        for (int64_t t = 1; t < S; ++t) {
+            float v = bf16_to_f32(Y[t * ldY + j]);
+            if (v < cmin) cmin = v;
+            if (v > cmax) cmax = v;
+        }
+        cmin += 0.0f; /* -0 becomes +0, so the result does not depend on */
+        cmax += 0.0f; /* which of two equal zeros was met first          */
+        if (first) {
+            m[j] = cmin;
+            M[j] = cmax;
+        } else {
+            float a = keep * m[j];
+            float b = gamma * cmin;
+            m[j] = a + b;
+            a = keep * M[j];
+            b = gamma * cmax;
+            M[j] = a + b;
+        }
+    }
+    return ORC_OK;
+}
+
+typedef struct {
+    float key;
+    int32_t j;
+} orc_rank_item;
+
+static int cmp_rank(const void *pa, const void *pb)
+{
+    const orc_rank_item *a = (const orc_rank_item *)pa;
+    const orc_rank_item *b = (const orc_rank_item *)pb;
+    if (a->key > b->key) return -1; /* larger aggregated range first */
+    if (a->key < b->key) return 1;
+    return (a->j > b->j) - (a->j < b->j); /* ties: lower feature first */
+}
+
+static int cmp_i32(const void *pa, const void *pb)
+{
+    int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+    return (a > b) - (a < b);
+}
+
+/*
+ * After the last sequence: R[i][j] = 2*max(-m, M); Rbar[j] = R[0][j] + R[1][j]
+ * + ... in ascending device order; the k features with the largest Rbar
+ * (ties to the lower index).  m, M: fp32 [N][E].  R (may be NULL): [N][E].
+ * idx_ranked (may be NULL): the k features by descending Rbar.  idx_sorted:
+ * the same set in ascending feature order.
+ */
+int orc_calibrate_finalize(const float *m, const float *M, int N, int E, int k,
+                           float *R, float *Rbar, int32_t *idx_sorted,
+                           int32_t *idx_ranked)
+{
+    if (!m || !M || !Rbar || N < 1 || E < 1 || k < 0 || k > E) return ORC_ERR_ARG;
+    if (k > 0 && !idx_sorted) return ORC_ERR_ARG;
+    for (int j = 0; j < E; ++j) {
+        float acc = 0.0f;
+        for (int i = 0; i < N; ++i) {
+            float lo = -m[(int64_t)i * E + j];
+            float hi = M[(int64_t)i * E + j];
+            float r = 2.0f * (lo > hi ? lo : hi);
+            r += 0.0f;
+            if (R) R[(int64_t)i * E + j] = r;
+            acc = (i == 0) ? r : acc + r;
+        }
+        Rbar[j] = acc;
+    }
+    orc_rank_item *items = (orc_rank_item *)malloc(sizeof(orc_rank_item) * (size_t)E);
+    if (!items) return ORC_ERR_ARG;
+    for (int j = 0; j < E; ++j) {
+        items[j].key = Rbar[j];
+        items[j].j = j;
+    }
+    qsort(items, (size_t)E, sizeof(orc_rank_item), cmp_rank);
+    for (int p = 0; p < k; ++p) {
+        if (idx_ranked) idx_ranked[p] = items[p].j;
+        idx_sorted[p] = items[p].j;
+    }
+    free(items);
+    if (k > 0) qsort(idx_sorted, (size_t)k, sizeof(int32_t), cmp_i32);
+    return ORC_OK;
+}
+
+/* ---- shared argument checks -------------------------------------------- */
+
+static int check_indices(const int32_t *idx, int k, int E)
+{
+    for (int p = 0; p < k; ++p) {
+        if (idx[p] < 0 || idx[p] >= E) return 0;
+        if (p > 0 && idx[p] <= idx[p - 1]) return 0;
+    }
+    return 1;
+}
+
+/* comp[c] = feature index of the c-th non-selected feature, ascending */
+static int32_t *build_compaction(const int32_t *idx, int k, int E)
+{
+    int r = E - k;
+    int32_t *comp = (int32_t *)malloc(sizeof(int32_t) * (size_t)(r > 0 ? r : 1));
+    if (!comp) return NULL;
+    int p = 0, c = 0;
+    for (int j = 0; j < E; ++j) {
+        if (p < k && idx[p] == j) {
+            ++p;
+        } else {
+            comp[c++] = j;
+        }
+    }
+    return comp;
+}
+
+/* ---- encode ------------------------------------------------------------ */
+
+static void encode_row(const uint16_t *y, int k, int r, int G,
+                       const int32_t *idx, const int32_t *comp,
+                       uint16_t *outl, uint8_t *codes, uint16_t *scale,
+                       uint16_t *zero)
+{
+    for (int p = 0; p < k; ++p) outl[p] = y[idx[p]]; /* verbatim 16-bit copy */
+
+    int cb = (r + 1) / 2;
+    memset(codes, 0, (size_t)cb);
+    int ng = (r + G - 1) / G;
+    for (int g = 0; g < ng; ++g) {
+        int c0 = g * G;
+        int c1 = c0 + G < r ? c0 + G : r;
+        float mn = bf16_to_f32(y[comp[c0]]);
+        float mx = mn;
+        for (int c = c0 + 1; c < c1; ++c) {
+            float v = bf16_to_f32(y[comp[c]]);
+            if (v < mn) mn = v;
+            if (v > mx) mx = v;
+        }
+        mn += 0.0f;
+        float span = mx - mn;
+        float s32 = span / 15.0f;
+        uint16_t sb = f32_to_bf16(s32);
+        float s = bf16_to_f32(sb);
+        zero[g] = f32_bits_hi(mn); /* mn is one of the bf16 inputs: exact */
+        if (s < 1e-30f) {
+            /* constant (or vanishing-range) group: all codes 0, scale 0 */
+            scale[g] = 0;
+            continue;
+        }
+        scale[g] = sb;
+        float inv = 1.0f / s;
+        for (int c = c0; c < c1; ++c) {
+            float v = bf16_to_f32(y[comp[c]]);
+            float d = v - mn;
+            float p = d * inv;
+            float q = rintf(p); /* ties to even */
+            if (q < 0.0f) q = 0.0f;
+            if (q > 15.0f) q = 15.0f;
+            unsigned code = (unsigned)q;
+            if (c & 1)
+                codes[c >> 1] |= (uint8_t)(code << 4);
+            else
+                codes[c >> 1] |= (uint8_t)code;
+        }
+    }
+}
+
+/*
+ * One device's partial sums Y bf16 [T][ldY] -> message sections (dense).
+ */
+int orc_encode(const uint16_t *Y, int64_t T, int64_t ldY, int E, int k, int G,
+               const int32_t *idx_sorted, uint16_t *outl, uint8_t *codes,
+               uint16_t *scale, uint16_t *zero, int threads)
+{
+    if (!Y || T < 0 || E < 1 || k < 0 || k > E || G < 2 || (G & 1) || ldY < E)
+        return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !scale || !zero)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int cb = (r + 1) / 2;
+    int ng = (r + G - 1) / G;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        encode_row(Y + t * ldY, k, r, G, idx_sorted, comp,
+                   outl ? outl + t * k : NULL, codes ? codes + t * cb : NULL,
+                   scale ? scale + t * ng : NULL, zero ? zero + t * ng : NULL);
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/* ---- decode + reduce --------------------------------------------------- */
+
+#define ORC_ACC_FP32 0
+#define ORC_ACC_BF16 1
+
+static float round_to_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
+
+/*
+ * N messages -> out [T][E] in original feature order.
+ * accum = ORC_ACC_FP32: acc = x_0; acc = acc + x_i (fp32), i ascending.
+ * accum = ORC_ACC_BF16: every term and every partial sum is rounded to bf16.
+ * out_fp32 != 0: out is float [T][E] (the accumulator as it is);
+ * otherwise out is bf16 (uint16) [T][E], the accumulator rounded once.
+ */
+int orc_decode_reduce(int N, int64_t T, int E, int k, int G,
+                      const int32_t *idx_sorted, const uint8_t *const *codes,
+                      const uint16_t *const *scale, const uint16_t *const *zero,
+                      const uint16_t *const *outl, int accum, int out_fp32,
+                      void *out, int threads)
+{
+    if (N < 1 || T < 0 || E < 1 || k < 0 || k > E || G < 2 || (G & 1) || !out)
+        return ORC_ERR_ARG;
+    if (accum != ORC_ACC_FP32 && accum != ORC_ACC_BF16) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !scale || !zero)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int cb = (r + 1) / 2;
+    int ng = (r + G - 1) / G;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float *of = out_fp32 ? (float *)out + t * E : NULL;
+        uint16_t *ob = out_fp32 ? NULL : (uint16_t *)out + t * E;
+        for (int col = 0; col < E; ++col) { /* col walks compacted, then outliers */
+            int j;
+            int is_outlier = col >= r;
+            j = is_outlier ? idx_sorted[col - r] : comp[col];
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                float x;
+                if (is_outlier) {
+                    x = bf16_to_f32(outl[i][t * k + (col - r)]);
+                } else {
+                    int c = col;
+                    uint8_t byte = codes[i][t * cb + (c >> 1)];
+                    unsigned code = (c & 1) ? (byte >> 4) : (byte & 0x0Fu);
+                    float s = bf16_to_f32(scale[i][t * ng + c / G]);
+                    float z = bf16_to_f32(zero[i][t * ng + c / G]);
+                    float prod = (float)code * s; /* exact: 4 bits x 8 bits */
+                    x = prod + z;
+                }
+                if (accum == ORC_ACC_BF16) {
+                    x = round_to_bf16(x);
+                    acc = (i == 0) ? x : round_to_bf16(acc + x);
+                } else {
+                    acc = (i == 0) ? x : acc + x;
+                }
+            }
+            if (of)
+                of[j] = acc;
+            else
+                ob[j] = f32_to_bf16(acc);
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
