@@ -1,0 +1,179 @@
+/*
+ * tpq.h -- C ABI of the low-bit tensor-parallel partial-sum codec for MI355X.
+ *
+ * The library implements, on one GPU, the per-device hot path of hybrid
+ * BF16 / 4-bit communication for tensor-parallel inference:
+ *
+ *   - offline calibration: per-device per-feature min/max moving averages
+ *     (paper Sec. 3 "Calibration", Eq. (1), (2)), symmetric ranges, their sum
+ *     over devices and the top-k features with the widest aggregated range
+ *     (Sec. 3 "Selecting High Precision Features");
+ *   - tpq_encode: the compression function C^(i) of Sec. 2 in the form of
+ *     Fig. 2 -- the k selected features of every row are sent verbatim in
+ *     BF16, the other r = E-k features as bit-packed 4-bit codes;
+ *   - tpq_decode_reduce: the decompression D^(i) of all N devices' messages
+ *     and their sum (Sec. 2; Fig. 2 caption), features back in original order.
+ *
+ * Quantiser (the workload definition's group-wise asymmetric form): the r
+ * non-selected features of a row, taken in ascending feature order
+ * ("compacted"), are cut into groups of G; per (row, group):
+ *     zero  = group minimum                      (a bf16 value, stored exactly)
+ *     scale = bf16_rne((max - min) / 15)         (0 if below 1e-30: constant group)
+ *     code  = clamp(rint((x - zero) * (1/float(scale))), 0, 15)   (ties to even)
+ *     x_hat = code * scale + zero
+ * All arithmetic is IEEE binary32 without contraction.
+ *
+ * Message of one device for one block = four row-major matrices:
+ *     outl  bf16  [T][k]             pitch_outl  bytes per row
+ *     codes u8    [T][ceil(r/2)]     pitch_codes bytes per row
+ *                 byte b = code 2b (bits 0-3) | code 2b+1 (bits 4-7); a final
+ *                 odd nibble and the pad bytes up to a multiple of 4 are zero
+ *     scale bf16  [T][ng]            pitch_meta  bytes per row, ng = ceil(r/G)
+ *     zero  bf16  [T][ng]            pitch_meta  bytes per row
+ *
+ * General rules
+ *   - Every function returns TPQ_OK (0) or a negative TPQ_ERR_* code; nothing
+ *     throws.  Argument errors are detected on the host before anything is
+ *     enqueued and leave all outputs untouched.
+ *   - Pointers marked [device] are device memory; [host] are host memory.  bf16
+ *     data is passed as uint16_t bit patterns.  Device pointers must be 16-byte
+ *     aligned, leading dimensions / pitches as stated per argument.
+ *   - The library never allocates, frees or retains device memory; all buffers
+ *     belong to the caller.  There is no global state; calls are re-entrant
+ *     across streams.
+ *   - Work is enqueued on the given HIP stream (a hipStream_t passed as void*,
+ *     NULL = the default stream) and the call returns without synchronising,
+ *     except tpq_plan_check.
+ *   - Inputs must be finite.  NaN / Inf give unspecified values, never a fault.
+ *   - T = 0 (or S = 0) is a successful no-op.
+ */
+#ifndef TPQ_H
+#define TPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TPQ_OK 0
+#define TPQ_ERR_NULL (-1)        /* a required pointer is NULL                         */
+#define TPQ_ERR_SHAPE (-2)       /* a size is out of range or inconsistent             */
+#define TPQ_ERR_INDEX (-3)       /* indices unsorted, duplicated or out of range       */
+#define TPQ_ERR_UNSUPPORTED (-4) /* bits != 4, G not in {32,64,128,256}, bad mode      */
+#define TPQ_ERR_ALIGN (-5)       /* pointer or pitch alignment                         */
+#define TPQ_ERR_WORKSPACE (-6)   /* workspace / plan buffer too small                  */
+#define TPQ_ERR_HIP (-7)         /* a HIP call failed; see tpq_last_hip_error()        */
+
+#define TPQ_ACC_FP32 0 /* x_0 + x_1 + ... in fp32, ascending device order              */
+#define TPQ_ACC_BF16 1 /* every term and every partial sum rounded to bf16             */
+#define TPQ_OUT_BF16 0
+#define TPQ_OUT_FP32 1
+
+#define TPQ_MAX_RANKS 64
+#define TPQ_MAX_E 32768
+
+/* Geometry of one block's message.  Fill with tpq_layout_init; the pitches may
+ * then be raised by the caller (multiples of 16 bytes). */
+typedef struct tpq_layout {
+    int32_t E;          /* features per row; multiple of 8, <= TPQ_MAX_E               */
+    int32_t k;          /* features kept in bf16, 0 <= k <= E                          */
+    int32_t G;          /* quantisation group size: 32, 64, 128 or 256                 */
+    int32_t bits;       /* code width; must be 4                                       */
+    int32_t r;          /* E - k                                                       */
+    int32_t ng;         /* ceil(r / G)                                                 */
+    int32_t code_bytes; /* ceil(r / 2)                                                 */
+    int32_t reserved;
+    int64_t pitch_codes; /* bytes per row of codes, multiple of 16, >= code_bytes      */
+    int64_t pitch_meta;  /* bytes per row of scale and of zero, multiple of 16         */
+    int64_t pitch_outl;  /* bytes per row of outl, multiple of 16                      */
+    int64_t wire_bytes_per_row; /* 2k + code_bytes + 4*ng: what really travels         */
+} tpq_layout;
+
+/* [host] Derive the layout for (E, k, G, bits).  Pure host function. */
+int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits);
+
+/* Average bits per communicated value.  payload = (16k + 4r)/E is the paper's
+ * accounting (abstract; Sec. 4: k = floor(E/64) gives 4.1875 < 4.2); wire adds
+ * the per-group scale and zero: 8 * wire_bytes_per_row / E. */
+double tpq_payload_bits(const tpq_layout *L);
+double tpq_wire_bits(const tpq_layout *L);
+
+const char *tpq_strerror(int code);
+int tpq_last_hip_error(void); /* hipError_t of the most recent TPQ_ERR_HIP on this thread */
+
+/* ---- plan: device tables derived from the static outlier index set -------
+ * The selected features are fixed across sequences and devices (Sec. 3), so
+ * the compaction map (which feature each compacted position reads) is built
+ * once per block and reused by every encode / decode_reduce call.
+ *   idx_sorted [device] int32[k], ascending, unique, in [0, E).
+ *   plan       [device] tpq_plan_bytes(L) bytes, 16-byte aligned, caller-owned.
+ * tpq_plan_build validates the indices on the device; encode / decode_reduce
+ * given a plan that is invalid (or built for another E, k, G) write nothing.
+ * tpq_plan_check synchronises the stream and reports TPQ_ERR_INDEX /
+ * TPQ_ERR_SHAPE for such a plan. */
+size_t tpq_plan_bytes(const tpq_layout *L);
+int tpq_plan_build(const tpq_layout *L, const int32_t *idx_sorted, void *plan,
+                   size_t plan_bytes, void *stream);
+int tpq_plan_check(const tpq_layout *L, const void *plan, void *stream);
+
+/* ---- calibration (Sec. 3, Eq. (1), (2)) -----------------------------------
+ * One call = one calibration sequence of one device:
+ *   cmin_j = min_t Y[t][j], cmax_j = max_t Y[t][j]     (a zero is taken as +0)
+ *   seq_index == 0:  m = cmin, M = cmax
+ *   otherwise:       m = (1-gamma)*m + gamma*cmin  (three rounded fp32 ops), same for M
+ *   Y         [device] bf16 [S][ldY], ldY in elements, multiple of 8, >= E
+ *   m, M      [device] fp32 [n_ranks][E]; row `rank` is updated
+ *   workspace [device] >= tpq_calibrate_workspace_bytes(S, E) bytes */
+size_t tpq_calibrate_workspace_bytes(int64_t S, int E);
+int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank,
+                  int n_ranks, int64_t seq_index, float gamma, float *m, float *M,
+                  void *workspace, size_t ws_bytes, void *stream);
+
+/* After the last sequence (Sec. 3):
+ *   R[i][j] = 2*max(-m[i][j], M[i][j]);  Rbar[j] = R[0][j] + R[1][j] + ... (fp32, ascending i)
+ *   the k features with the largest Rbar (ties: lower index first)
+ *   R          [device] fp32 [n_ranks][E], may be NULL
+ *   Rbar       [device] fp32 [E]
+ *   idx_sorted [device] int32[k], ascending feature order (what tpq_plan_build takes)
+ *   idx_ranked [device] int32[k], by descending Rbar; may be NULL
+ *   workspace  [device] >= tpq_calibrate_finalize_workspace_bytes(E) bytes */
+size_t tpq_calibrate_finalize_workspace_bytes(int E);
+int tpq_calibrate_finalize(const float *m, const float *M, int n_ranks, int E, int k,
+                           float *R, float *Rbar, int32_t *idx_sorted,
+                           int32_t *idx_ranked, void *workspace, size_t ws_bytes,
+                           void *stream);
+
+/* ---- encode (Sec. 2 C^(i); Fig. 2) ----------------------------------------
+ * Encodes n_ranks partial-sum tensors in one launch (n_ranks = 1 is a single
+ * device's real call; larger values simulate several devices on one GPU).
+ *   Y     [host] array of n_ranks [device] pointers, each bf16 [T][ldY]
+ *   ldY   elements, multiple of 8, >= E
+ *   codes, scale, zero, outl: [host] arrays of n_ranks [device] pointers to the
+ *         message sections (see the layout above); outl entries are ignored when
+ *         k = 0, the other three when k = E
+ *   plan  [device] built by tpq_plan_build for the same layout */
+int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y,
+               int64_t ldY, int n_ranks, int64_t T, uint8_t *const *codes,
+               uint16_t *const *scale, uint16_t *const *zero, uint16_t *const *outl,
+               void *stream);
+
+/* ---- decode + reduce (Sec. 2 D^(i) and the sum; Fig. 2 caption) ------------
+ * out[t][j] = sum over the n_ranks messages of x_hat (selected features: the
+ * bf16 value itself), in ascending device order, in original feature order.
+ *   accum     TPQ_ACC_FP32 or TPQ_ACC_BF16
+ *   out_dtype TPQ_OUT_BF16: out is bf16 [T][ldOut] (fp32 accumulator rounded once);
+ *             TPQ_OUT_FP32: out is fp32 [T][ldOut] (needs accum = TPQ_ACC_FP32 or
+ *             gives the bf16-valued accumulator widened)
+ *   ldOut     elements; multiple of 8 (bf16) or 4 (fp32), >= E */
+int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
+                      const uint8_t *const *codes, const uint16_t *const *scale,
+                      const uint16_t *const *zero, const uint16_t *const *outl,
+                      int accum, int out_dtype, void *out, int64_t ldOut,
+                      void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPQ_H */

@@ -61,7 +61,10 @@ def _load():
 
 
 def max_threads() -> int:
-    return int(_load().orc_max_threads())
+    """Host threads the timed runs may use: OMP_NUM_THREADS if set, else the core count."""
+    procs = int(_load().orc_max_threads())
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    return max(1, min(procs, int(env))) if env.isdigit() else procs
 
 
 def _ptr(a):

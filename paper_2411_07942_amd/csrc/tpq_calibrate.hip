@@ -1,0 +1,207 @@
+// tpq_calibrate kernels: per-feature min / max of a calibration sequence, the
+// moving-average update of Eq. (1), (2), and the final range aggregation and top-k
+// selection (paper Sec. 3).
+#include "tpq_device.h"
+#include "tpq_internal.h"
+
+namespace tpq {
+
+constexpr int kStripLanes = 64;        // lanes across columns; 8 columns per lane
+constexpr int kStripCols = 8 * kStripLanes;
+constexpr int kWavesPerBlock = 4;      // waves of a block share columns, split rows
+
+// How many row slices ("parts") a sequence of S rows is cut into.  Each
+// (column strip, part) is one workgroup; the count only depends on (S, E), so
+// the workspace size does too.
+int calibrate_parts(int64_t S, int E)
+{
+    const int strips = (E + kStripCols - 1) / kStripCols;
+    int64_t target = (4096 + strips - 1) / strips;       // aim at ~4096 workgroups
+    int64_t max_parts = (S + 31) / 32;                   // at least 32 rows per part
+    if (max_parts < 1) max_parts = 1;
+    int64_t parts = target < max_parts ? target : max_parts;
+    if (parts < 1) parts = 1;
+    return static_cast<int>(parts);
+}
+
+// Column min / max over one slice of rows.  Lane l of every wave owns columns
+// 8*(64*blockIdx.x + l) .. +7 and keeps 8 running minima and maxima in registers;
+// the block's 4 waves take interleaved rows and are combined through LDS.
+// Partials go to ws as [part][0 = min, 1 = max][E].
+__global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax(
+    const uint16_t *__restrict__ Y, int64_t S, int64_t ldY, int E, int rows_per_part,
+    float *__restrict__ ws)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col8 = blockIdx.x * kStripLanes + lane;  // which group of 8 columns
+    const bool live = col8 * 8 < E;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.y) * rows_per_part;
+    int64_t row1 = row0 + rows_per_part;
+    if (row1 > S) row1 = S;
+
+    float mn[8], mx[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        mn[e] = 3.4028235e38f;   // every finite bf16 value lies inside (-FLT_MAX, FLT_MAX)
+        mx[e] = -3.4028235e38f;
+    }
+    if (live) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(Y + col8 * 8);
+        const int64_t stride = ldY / 8;  // in uint4
+#pragma unroll 4
+        for (int64_t t = row0 + wave; t < row1; t += kWavesPerBlock) {
+            const uint4 v = p[t * stride];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = bf16_lo_to_f32(w[e]);
+                const float hi = bf16_hi_to_f32(w[e]);
+                mn[2 * e] = fminf(mn[2 * e], lo);
+                mx[2 * e] = fmaxf(mx[2 * e], lo);
+                mn[2 * e + 1] = fminf(mn[2 * e + 1], hi);
+                mx[2 * e + 1] = fmaxf(mx[2 * e + 1], hi);
+            }
+        }
+    }
+
+    __shared__ float red[kWavesPerBlock][2][8][kStripLanes];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        red[wave][0][e][lane] = mn[e];
+        red[wave][1][e][lane] = mx[e];
+    }
+    __syncthreads();
+    if (wave == 0 && live) {
+        float *out_mn = ws + (static_cast<int64_t>(blockIdx.y) * 2 + 0) * E + col8 * 8;
+        float *out_mx = ws + (static_cast<int64_t>(blockIdx.y) * 2 + 1) * E + col8 * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = red[0][0][e][lane], b = red[0][1][e][lane];
+#pragma unroll
+            for (int w2 = 1; w2 < kWavesPerBlock; ++w2) {
+                a = fminf(a, red[w2][0][e][lane]);
+                b = fmaxf(b, red[w2][1][e][lane]);
+            }
+            out_mn[e] = a;
+            out_mx[e] = b;
+        }
+    }
+}
+
+// Combine the parts and apply Eq. (1), (2) to one device's state.
+__global__ void k_ema(const float *__restrict__ ws, int parts, int E, int first, float gamma,
+                      float *__restrict__ m, float *__restrict__ M)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= E) return;
+    float cmin = ws[j], cmax = ws[E + j];
+    for (int p = 1; p < parts; ++p) {
+        cmin = fminf(cmin, ws[(2 * static_cast<int64_t>(p)) * E + j]);
+        cmax = fmaxf(cmax, ws[(2 * static_cast<int64_t>(p) + 1) * E + j]);
+    }
+    cmin += 0.0f;  // a zero is taken as +0
+    cmax += 0.0f;
+    if (first) {
+        m[j] = cmin;
+        M[j] = cmax;
+    } else {
+        const float keep = 1.0f - gamma;
+        float x = keep * m[j];
+        float y = gamma * cmin;
+        m[j] = x + y;
+        x = keep * M[j];
+        y = gamma * cmax;
+        M[j] = x + y;
+    }
+}
+
+int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
+                         float gamma, float *m, float *M, float *ws, hipStream_t s)
+{
+    const int parts = calibrate_parts(S, E);
+    const int rows_per_part = static_cast<int>((S + parts - 1) / parts);
+    // the last parts may be empty when S is not a multiple; recompute the live count
+    const int live_parts = static_cast<int>((S + rows_per_part - 1) / rows_per_part);
+    const dim3 grid((E + kStripCols - 1) / kStripCols, live_parts);
+    k_colminmax<<<grid, kStripLanes * kWavesPerBlock, 0, s>>>(Y, S, ldY, E, rows_per_part, ws);
+    k_ema<<<(E + 255) / 256, 256, 0, s>>>(ws, live_parts, E, first, gamma, m, M);
+    return hip_result(hipGetLastError());
+}
+
+// ---- finalize -------------------------------------------------------------------
+
+// R = 2*max(-m, M) per device, Rbar = sum over devices in ascending order.
+__global__ void k_ranges(const float *__restrict__ m, const float *__restrict__ M, int N, int E,
+                         float *__restrict__ R, float *__restrict__ Rbar)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= E) return;
+    float acc = 0.f;
+    for (int i = 0; i < N; ++i) {
+        const float lo = -m[static_cast<int64_t>(i) * E + j];
+        const float hi = M[static_cast<int64_t>(i) * E + j];
+        float r = 2.0f * (lo > hi ? lo : hi);
+        r += 0.0f;
+        if (R) R[static_cast<int64_t>(i) * E + j] = r;
+        acc = i == 0 ? r : acc + r;
+    }
+    Rbar[j] = acc;
+}
+
+// Rank of feature j in the order (Rbar descending, index ascending), by counting
+// the features that come before it.  E <= 32768 and this runs once per block of
+// the model, offline, so the quadratic count is affordable and needs no sort.
+__global__ __launch_bounds__(256) void k_rank(const float *__restrict__ Rbar, int E, int k,
+                                              int32_t *__restrict__ rank_of,
+                                              int32_t *__restrict__ idx_ranked)
+{
+    __shared__ float tile[256];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const float mine = j < E ? Rbar[j] : 0.f;
+    int before = 0;
+    for (int base = 0; base < E; base += 256) {
+        const int o = base + threadIdx.x;
+        tile[threadIdx.x] = o < E ? Rbar[o] : -1.0f;  // ranges are >= 0
+        __syncthreads();
+        const int n = E - base < 256 ? E - base : 256;
+        for (int q = 0; q < n; ++q) {
+            const float other = tile[q];
+            before += (other > mine) || (other == mine && base + q < j);
+        }
+        __syncthreads();
+    }
+    if (j < E) {
+        rank_of[j] = before;
+        if (before < k && idx_ranked) idx_ranked[before] = j;
+    }
+}
+
+// Ascending list of the selected features: position = selected features below j.
+__global__ __launch_bounds__(256) void k_select_sorted(const int32_t *__restrict__ rank_of, int E,
+                                                       int k, int32_t *__restrict__ idx_sorted)
+{
+    __shared__ int32_t tile[256];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    int below = 0;
+    for (int base = 0; base <= static_cast<int>(blockIdx.x) * 256; base += 256) {
+        const int o = base + threadIdx.x;
+        tile[threadIdx.x] = (o < E && rank_of[o] < k) ? 1 : 0;
+        __syncthreads();
+        for (int q = 0; q < 256; ++q) below += (base + q < j) ? tile[q] : 0;
+        __syncthreads();
+    }
+    if (j < E && rank_of[j] < k) idx_sorted[below] = j;
+}
+
+int launch_finalize(const float *m, const float *M, int N, int E, int k, float *R, float *Rbar,
+                    int32_t *idx_sorted, int32_t *idx_ranked, int32_t *ws, hipStream_t s)
+{
+    const int blocks = (E + 255) / 256;
+    k_ranges<<<blocks, 256, 0, s>>>(m, M, N, E, R, Rbar);
+    k_rank<<<blocks, 256, 0, s>>>(Rbar, E, k, ws, idx_ranked);
+    if (k > 0) k_select_sorted<<<blocks, 256, 0, s>>>(ws, E, k, idx_sorted);
+    return hip_result(hipGetLastError());
+}
+
+}  // namespace tpq
