@@ -99,7 +99,7 @@ int tpq_last_hip_error(void) { return g_last_hip_error; }
 size_t tpq_plan_bytes(const tpq_layout *L)
 {
     if (check_layout(L) != TPQ_OK) return 0;
-    size_t n = sizeof(PlanHeader) + idx_bytes_of(L->k) + 16ull * chunks_padded_of(L->r);
+    const size_t n = static_cast<size_t>(plan_offsets(L->k, L->r).total);
     return (n + 255) / 256 * 256;
 }
 

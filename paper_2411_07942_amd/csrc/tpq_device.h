@@ -26,6 +26,23 @@ __device__ __forceinline__ float round_to_bf16(float f)
     return __uint_as_float(u & 0xFFFF0000u);
 }
 
+// 128-bit vector that the compiler may load / store as one instruction
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// ... also at 2-byte alignment (gfx9 global memory accepts unaligned accesses in
+// the HSA configuration; the hardware splits an access that crosses a cache line)
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+
+// Orders one wavefront's LDS traffic: writes by any lane before this point are
+// seen by reads of any lane after it.  LDS operations of a wave execute in issue
+// order, so only the compiler has to be held back.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---- DPP lane exchange ---------------------------------------------------------
 // dpp_ctrl encodings: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E,
 // row_ror:n = 0x120 + n (rotate within a row of 16 lanes), row_half_mirror = 0x141
@@ -33,8 +50,8 @@ __device__ __forceinline__ float round_to_bf16(float f)
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v)
 {
-    int x = __float_as_int(v);
-    return __int_as_float(__builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false));
+    // every lane has a source under these controls, so the "old" operand is never used
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
 // min and max over aligned groups of LPG lanes (LPG in {4, 8, 16, 32}); every lane
@@ -60,6 +77,32 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx)
     if (LPG == 32) {
         mn = fminf(mn, __shfl_xor(mn, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    }
+}
+
+// The same reduction for N independent (min, max) pairs at once, stage by stage, so
+// that consecutive DPP instructions never depend on each other.
+template <int LPG, int N>
+__device__ __forceinline__ void group_minmax_n(float (&mn)[N], float (&mx)[N])
+{
+    static_assert(LPG == 4 || LPG == 8 || LPG == 16 || LPG == 32, "lanes per group");
+#define TPQ_STAGE(CTRL)                                                  \
+    _Pragma("unroll") for (int i = 0; i < N; ++i)                        \
+    {                                                                    \
+        mn[i] = fminf(mn[i], dpp_f32<CTRL>(mn[i]));                      \
+        mx[i] = fmaxf(mx[i], dpp_f32<CTRL>(mx[i]));                      \
+    }
+    TPQ_STAGE(0xB1)
+    TPQ_STAGE(0x4E)
+    if (LPG == 8) { TPQ_STAGE(0x141) }
+    if (LPG >= 16) { TPQ_STAGE(0x124) TPQ_STAGE(0x128) }
+#undef TPQ_STAGE
+    if (LPG == 32) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            mn[i] = fminf(mn[i], __shfl_xor(mn[i], 16, 64));
+            mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 16, 64));
+        }
     }
 }
 

@@ -126,6 +126,218 @@ __global__ __launch_bounds__(64) void k_encode_row(EncodeArgs a, RankPtrs Yp, Ra
     }
 }
 
+// ---------------------------------------------------------------------------
+// Streaming kernel (the fast path).
+//
+// A task is one segment of one row of one rank: P passes of 64 chunks.  Groups
+// never straddle a pass (64 chunks = 512 features, a multiple of every G), so
+// segments are independent.  One wavefront per task, four tasks per workgroup,
+// no workgroup barrier: all LDS use is private to a wave.
+//
+//   A. the columns of the row that the segment covers are fetched with aligned,
+//      coalesced 128-bit loads (all of a lane's loads in flight together) and
+//      parked in LDS;
+//   B. the few chunks that an outlier splits (at most k + 1 per row) are gathered
+//      element by element from LDS by as many lanes and parked in an LDS patch
+//      area; the selected columns themselves go to the outlier section;
+//   C. every lane reads its 8 consecutive compacted features with one 128-bit LDS
+//      read at the chunk's start column -- 2-byte aligned, since removing the
+//      selected columns shifts the compacted stream by their count; owners of
+//      split chunks take theirs from the patch area;
+//   D. lane-local min / max of 8 features, DPP reduction over the group's lanes,
+//      leaders park (min, max) in LDS;
+//   E. one lane per group derives zero, bf16 scale and reciprocal (two IEEE
+//      divisions per group instead of per lane) and stores scale / zero;
+//   F. quantise from registers, pack 8 nibbles per lane, coalesced store.
+// ---------------------------------------------------------------------------
+template <int LPG, int P>
+__global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp, RankPtrs codesp,
+                                                       RankPtrs scalep, RankPtrs zerop,
+                                                       RankPtrs outlp)
+{
+    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
+    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
+        ph->G != a.G)
+        return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // grid: x = groups of 4 rows, y = rank, z = segment of the row
+    const uint32_t t = blockIdx.x * 4u + wave;
+    if (t >= static_cast<uint32_t>(a.T)) return;
+    const uint32_t rank = blockIdx.y;
+    const uint32_t seg = blockIdx.z;
+
+    const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
+    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
+    const uint16_t *pass_irr = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_irr_offset);
+    const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_col_offset);
+    const u32x4 *irr_src = reinterpret_cast<const u32x4 *>(a.plan + ph->irr_src_offset);
+
+    const uint32_t pass0 = seg * P;
+    const uint32_t passes_total = static_cast<uint32_t>(a.chunks_padded) >> 6;
+    const uint32_t n_pass = passes_total - pass0 < P ? passes_total - pass0 : P;
+    const bool last_seg = pass0 + n_pass == passes_total;
+
+    // columns [col_lo, col_hi) of the row are staged; both are multiples of 8
+    const uint32_t c_first = pass_col[pass0], c_next = pass_col[pass0 + n_pass];
+    const uint32_t col_lo = seg == 0 ? 0u : (c_first & ~7u);
+    const uint32_t col_hi = last_seg ? static_cast<uint32_t>(a.E) : ((c_next + 7u) & ~7u);
+    const uint32_t n16 = (col_hi - col_lo) >> 3;
+    // selected columns owned by this segment
+    const uint32_t p_lo = seg == 0 ? 0u : c_first - 512u * pass0;
+    const uint32_t p_hi = last_seg ? static_cast<uint32_t>(a.k) : c_next - 512u * (pass0 + n_pass);
+
+    constexpr int GPS = 64 * P / LPG;  // groups per segment
+    constexpr int META16 = (GPS * 8 + 15) / 16;
+    extern __shared__ u32x4 smem_stream[];
+    u32x4 *stage = smem_stream + wave * (a.stage_chunks + a.patch_slots + META16);
+    u32x4 *patch = stage + a.stage_chunks;
+    float2 *meta = reinterpret_cast<float2 *>(patch + a.patch_slots);
+    const uint16_t *stage16 = reinterpret_cast<const uint16_t *>(stage);
+
+    // A: the row slice -> LDS (index clamped instead of masked: no divergence)
+    {
+        const u32x4 *yrow = reinterpret_cast<const u32x4 *>(
+                                static_cast<const uint16_t *>(Yp.p[rank]) +
+                                static_cast<int64_t>(t) * a.ldY) + (col_lo >> 3);
+        constexpr int S = P + 1;
+        u32x4 rbuf[S];
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            const uint32_t c = min(j * 64u + lane, n16 - 1u);
+            rbuf[j] = __builtin_nontemporal_load(yrow + c);
+        }
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            const uint32_t c = min(j * 64u + lane, n16 - 1u);
+            stage[c] = rbuf[j];
+        }
+        for (uint32_t c = S * 64u + lane; c < n16; c += 64) stage[c] = yrow[c];
+    }
+    uint32_t cp[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        cp[p] = static_cast<uint32_t>(p) < n_pass
+                    ? cpos[(pass0 + p) * 64u + lane]
+                    : (kNotRegular | (kNoSlot << 16) | (col_hi - 8u));
+    const uint32_t q_lo = pass_irr[pass0], q_hi = pass_irr[pass0 + n_pass];
+    wave_lds_fence();
+
+    // B: split chunks of this segment -> patch area; selected columns -> outlier section
+    for (uint32_t q = q_lo + lane; q < q_hi; q += 64) {
+        const u32x4 tab = irr_src[q];
+        u32x4 g;
+        g.x = stage16[(tab.x & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.x >> 16) - col_lo]) << 16);
+        g.y = stage16[(tab.y & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.y >> 16) - col_lo]) << 16);
+        g.z = stage16[(tab.z & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.z >> 16) - col_lo]) << 16);
+        g.w = stage16[(tab.w & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.w >> 16) - col_lo]) << 16);
+        patch[q - q_lo] = g;
+    }
+    if (p_lo < p_hi) {
+        uint16_t *outl = reinterpret_cast<uint16_t *>(
+            static_cast<uint8_t *>(const_cast<void *>(outlp.p[rank])) +
+            static_cast<int64_t>(t) * a.pitch_outl);
+        for (uint32_t p = p_lo + lane; p < p_hi; p += 64) outl[p] = stage16[idx[p] - col_lo];
+    }
+
+    // C: 8 consecutive compacted features per lane and pass
+    u32x4 v[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        v[p] = *reinterpret_cast<const u32x4_a2 *>(stage16 + ((cp[p] & 0xFFFFu) - col_lo));
+    wave_lds_fence();
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint32_t slot = (cp[p] >> 16) & 0x7FFFu;
+        if ((cp[p] & kNotRegular) && slot != kNoSlot) v[p] = patch[slot - q_lo];
+    }
+
+    // D: group min / max
+    {
+        float mn[P], mx[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const float a0 = bf16_lo_to_f32(v[p].x), a1 = bf16_hi_to_f32(v[p].x);
+            const float a2 = bf16_lo_to_f32(v[p].y), a3 = bf16_hi_to_f32(v[p].y);
+            const float a4 = bf16_lo_to_f32(v[p].z), a5 = bf16_hi_to_f32(v[p].z);
+            const float a6 = bf16_lo_to_f32(v[p].w), a7 = bf16_hi_to_f32(v[p].w);
+            mn[p] = fminf(fminf(fminf(a0, a1), fminf(a2, a3)), fminf(fminf(a4, a5), fminf(a6, a7)));
+            mx[p] = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), fmaxf(fmaxf(a4, a5), fmaxf(a6, a7)));
+            if ((cp[p] >> 16) == (0x8000u | kNoSlot)) {  // beyond the row: neutral
+                mn[p] = 3.4028235e38f;
+                mx[p] = -3.4028235e38f;
+            }
+        }
+        group_minmax_n<LPG, P>(mn, mx);
+        if ((lane % LPG) == 0) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) meta[(p * 64 + lane) / LPG] = make_float2(mn[p], mx[p]);
+        }
+    }
+    wave_lds_fence();
+
+    // E: zero, scale, reciprocal -- one lane per group
+    {
+        uint16_t *scale = reinterpret_cast<uint16_t *>(
+            static_cast<uint8_t *>(const_cast<void *>(scalep.p[rank])) +
+            static_cast<int64_t>(t) * a.pitch_meta);
+        uint16_t *zero = reinterpret_cast<uint16_t *>(
+            static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
+            static_cast<int64_t>(t) * a.pitch_meta);
+        const uint32_t g0 = pass0 * (64 / LPG);
+        for (uint32_t gl = lane; gl < static_cast<uint32_t>(GPS); gl += 64) {
+            const uint32_t g = g0 + gl;
+            if (g < static_cast<uint32_t>(a.ng)) {
+                const float2 mm = meta[gl];
+                const float mn = mm.x + 0.0f;  // a zero minimum is stored as +0
+                const float span = mm.y - mn;
+                const float s32 = span / 15.0f;
+                const uint32_t sb = f32_to_bf16_bits(s32);
+                const float s = bf16_bits_to_f32(sb);
+                const bool constant = s < 1e-30f;
+                const float inv = constant ? 0.0f : 1.0f / s;
+                scale[g] = constant ? uint16_t(0) : static_cast<uint16_t>(sb);
+                zero[g] = static_cast<uint16_t>(__float_as_uint(mn) >> 16);
+                meta[gl] = make_float2(mn, inv);
+            }
+        }
+    }
+    wave_lds_fence();
+
+    // F: quantise and pack.  (x - zero) * inv lies in [0, 15.06] for finite input
+    // (scale is (max - min) / 15 rounded to 8 significant bits), so the rounded
+    // value needs no clamp to stay a 4-bit code.
+    uint32_t *codes = reinterpret_cast<uint32_t *>(
+        static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
+        static_cast<int64_t>(t) * a.pitch_codes);
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint32_t chunk = (pass0 + p) * 64u + lane;
+        const float2 mi = meta[(p * 64 + lane) / LPG];
+        const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+        float h[2];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            float q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t word = wv[half * 2 + (e >> 1)];
+                const float x = (e & 1) ? bf16_hi_to_f32(word) : bf16_lo_to_f32(word);
+                const float d = x - mi.x;
+                const float pr = d * mi.y;
+                q[e] = rintf(pr);
+            }
+            // four codes -> one 16-bit integer, exactly, in fp32
+            h[half] = __builtin_fmaf(q[3], 4096.0f,
+                                     __builtin_fmaf(q[2], 256.0f, __builtin_fmaf(q[1], 16.0f, q[0])));
+        }
+        uint32_t w = static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16);
+        const int n_valid = a.r - 8 * static_cast<int>(chunk);
+        if (n_valid < 8) w &= (1u << (4 * (n_valid & 7))) - 1u;
+        if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w, codes + chunk);
+    }
+}
+
 static size_t encode_row_lds(const EncodeArgs &a, int lpg)
 {
     const size_t groups_padded = static_cast<size_t>(a.chunks_padded) / lpg;
@@ -133,14 +345,86 @@ static size_t encode_row_lds(const EncodeArgs &a, int lpg)
     return static_cast<size_t>(a.E) * 2 + (meta + 15) / 16 * 16;
 }
 
-int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
+// Passes per segment the streaming kernel is compiled for.
+static int pick_seg_passes(int passes, int *segs)
+{
+    static const int kP[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    const int n_seg = (passes + 15) / 16;
+    const int need = (passes + n_seg - 1) / n_seg;
+    *segs = n_seg;
+    for (int p : kP)
+        if (p >= need) {
+            *segs = (passes + p - 1) / p;
+            return p;
+        }
+    return 16;
+}
+
+template <int LPG>
+static hipError_t launch_stream_lpg(EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
+                                    const RankPtrs &scale, const RankPtrs &zero,
+                                    const RankPtrs &outl, hipStream_t s)
+{
+    const int P = a.seg_passes;
+    const size_t meta16 = (static_cast<size_t>(64 * P / LPG) * 8 + 15) / 16;
+    const size_t lds = 4 * 16 * (static_cast<size_t>(a.stage_chunks) + a.patch_slots + meta16);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>((a.T + 3) / 4), static_cast<unsigned>(a.n_ranks),
+                    static_cast<unsigned>(a.segs));
+    hipError_t e = hipSuccess;
+#define TPQ_CASE(PP)                                                                         \
+    case PP:                                                                                 \
+        if (lds > 65536)                                                                     \
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_stream<LPG, PP>), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,              \
+                                    static_cast<int>(lds));                                  \
+        if (e == hipSuccess)                                                                 \
+            k_encode_stream<LPG, PP><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl); \
+        break;
+    switch (P) {
+        TPQ_CASE(1) TPQ_CASE(2) TPQ_CASE(3) TPQ_CASE(4) TPQ_CASE(5) TPQ_CASE(6) TPQ_CASE(8)
+        TPQ_CASE(10) TPQ_CASE(12) TPQ_CASE(16)
+    default: return hipErrorInvalidValue;
+    }
+#undef TPQ_CASE
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+int launch_encode(const EncodeArgs &a_in, const RankPtrs &Y, const RankPtrs &codes,
                   const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl,
                   hipStream_t s)
 {
+    EncodeArgs a = a_in;
     const int lpg = a.G / 8;
+    hipError_t e = hipSuccess;
+
+    // Streaming path: needs at least one quantised feature and an LDS patch area
+    // (k + 1 slots of 16 bytes per wave) of moderate size.
+    const int slots = irr_slots_of(a.k, a.r);
+    if (a.r > 0 && slots <= 512) {
+        a.seg_passes = pick_seg_passes(a.chunks_padded / 64, &a.segs);
+        a.patch_slots = slots;
+        // a segment's slice: its 64*P chunks, shifted by at most k columns, plus rounding
+        {
+            const int whole = a.E / 8;
+            const int need = 64 * a.seg_passes + (a.k + 7) / 8 + 2;
+            a.stage_chunks = need < whole ? need : whole;
+        }
+        a.n_tasks = a.T * a.n_ranks * a.segs;
+        switch (lpg) {
+        case 4: e = launch_stream_lpg<4>(a, Y, codes, scale, zero, outl, s); break;
+        case 8: e = launch_stream_lpg<8>(a, Y, codes, scale, zero, outl, s); break;
+        case 16: e = launch_stream_lpg<16>(a, Y, codes, scale, zero, outl, s); break;
+        case 32: e = launch_stream_lpg<32>(a, Y, codes, scale, zero, outl, s); break;
+        default: return TPQ_ERR_UNSUPPORTED;
+        }
+        return hip_result(e);
+    }
+
+    // General path: the whole row staged in LDS, any number of selected features.
     const dim3 grid(static_cast<unsigned>(a.T * a.n_ranks));
     const size_t lds = encode_row_lds(a, lpg);
-    hipError_t e = hipSuccess;
 #define TPQ_LAUNCH(LPG)                                                                      \
     do {                                                                                     \
         if (lds > 65536)                                                                     \

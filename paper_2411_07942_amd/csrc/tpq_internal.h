@@ -10,18 +10,38 @@ namespace tpq {
 
 // ---- plan (device-resident tables derived from the outlier index set) --------
 //
-// Layout in the caller's plan buffer:
-//   PlanHeader                         64 bytes
-//   idx     int32 [k rounded up to 4]  the selected features, ascending
-//   src_of  uint16[chunks_padded * 8]  src_of[c] = feature index of compacted
-//                                      position c; positions >= r repeat the
-//                                      last real one (harmless for min / max)
 // A "chunk" is 8 consecutive compacted features: what one lane handles, and one
-// 32-bit word of packed codes.  chunks_padded rounds the chunk count up to a
-// whole number of 64-lane passes.
-constexpr uint32_t kPlanMagic = 0x51505431u;  // "1TPQ"
+// 32-bit word of packed codes.  A "pass" is 64 chunks (one wavefront).
+// chunks_padded rounds the chunk count up to whole passes.
+//
+// Layout in the caller's plan buffer (every table starts on a 16-byte boundary):
+//   PlanHeader                          64 bytes
+//   idx      int32 [k rounded up to 4]  the selected features, ascending
+//   src_of   uint16[chunks_padded * 8]  src_of[c] = feature index of compacted
+//                                       position c; positions >= r repeat the
+//                                       last real one (harmless for min / max)
+//   cpos     uint32[chunks_padded]      per chunk: bits 15..0 = a column from which
+//                                       16 bytes can always be read; for a "regular"
+//                                       chunk (its 8 features are consecutive
+//                                       columns) that is the chunk's first column
+//                                       and the whole word is just that.  Bit 31 set:
+//                                       an outlier splits the chunk or it is the
+//                                       ragged last one ("irregular"; bits 30..16 =
+//                                       its slot q in irr / irr_src), or the chunk
+//                                       lies beyond the row (slot = kNoSlot).
+//   flags    uint16[chunks_padded]      scratch of the build (1 = irregular)
+//   irr      uint16[chunks_padded]      irr[q] = chunk number of the q-th irregular
+//                                       chunk, ascending; at most k + 1 of them
+//   pass_irr uint16[passes + 1]         irregular chunks below pass p
+//   irr_src  uint16[8 * slots]          the 8 feature indices of irregular chunk q
+//   pass_col uint16[passes + 1]         column of the first feature of pass p
+//                                       (pass_col[passes] = E)
+constexpr uint32_t kPlanMagic = 0x51505433u;  // "3TPQ"
 constexpr int kPlanOk = 1;
 constexpr int kPlanBadIndex = 2;
+constexpr uint32_t kNotRegular = 0x80000000u;
+constexpr uint32_t kNoSlot = 0x7FFFu;
+// beyond the row: flag + no slot; the low bits then hold column E - 8
 
 struct PlanHeader {
     uint32_t magic;
@@ -31,13 +51,46 @@ struct PlanHeader {
     int32_t chunks_padded;  // chunks rounded up to a multiple of 64
     int32_t idx_offset;     // byte offsets from the start of the plan
     int32_t src_offset;
-    int32_t pad[6];
+    int32_t pos_offset;
+    int32_t pass_col_offset;
+    int32_t irr_offset;
+    int32_t pass_irr_offset;
+    int32_t n_irr;
+    int32_t irr_src_offset;
 };
 static_assert(sizeof(PlanHeader) == 64, "plan header is 64 bytes");
 
 inline int chunks_of(int r) { return (r + 7) / 8; }
 inline int chunks_padded_of(int r) { return (chunks_of(r) + 63) / 64 * 64; }
 inline int idx_bytes_of(int k) { return ((k + 3) / 4 * 4) * 4; }
+
+// an upper bound of the irregular chunks of a row that the host can compute
+inline int irr_slots_of(int k, int r)
+{
+    const int c = chunks_of(r);
+    return k + 1 < c ? k + 1 : c;
+}
+
+inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
+
+struct PlanOffsets {
+    int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src, total;
+};
+inline PlanOffsets plan_offsets(int k, int r)
+{
+    const int cp = chunks_padded_of(r);
+    PlanOffsets o;
+    o.idx = sizeof(PlanHeader);
+    o.src = o.idx + idx_bytes_of(k);
+    o.pos = o.src + 16 * cp;
+    o.flags = o.pos + 4 * cp;
+    o.irr = o.flags + 2 * cp;
+    o.pass_irr = o.irr + 2 * cp;
+    o.pass_col = o.pass_irr + pass_tab_bytes_of(r);
+    o.irr_src = o.pass_col + pass_tab_bytes_of(r);
+    o.total = o.irr_src + 16 * irr_slots_of(k, r);
+    return o;
+}
 
 // ---- kernel argument blocks -------------------------------------------------
 
@@ -51,6 +104,10 @@ struct EncodeArgs {
     int32_t n_ranks;
     int64_t T, ldY;
     int64_t pitch_codes, pitch_meta, pitch_outl;
+    // streaming kernels: a row is cut into `segs` segments of `seg_passes` passes;
+    // stage_chunks = 16-byte units of LDS each wave has for its slice of the row
+    int32_t segs, seg_passes, patch_slots, stage_chunks;
+    int64_t n_tasks;  // n_ranks * T * segs
 };
 
 struct DecodeArgs {
@@ -60,6 +117,8 @@ struct DecodeArgs {
     int64_t T, ldOut;
     int64_t pitch_codes, pitch_meta, pitch_outl;
     void *out;
+    int32_t segs, seg_passes, patch_slots, stage_chunks;
+    int64_t n_tasks;  // T * segs
 };
 
 // ---- host-side helpers --------------------------------------------------------
