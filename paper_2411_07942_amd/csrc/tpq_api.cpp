@@ -99,7 +99,7 @@ int tpq_last_hip_error(void) { return g_last_hip_error; }
 size_t tpq_plan_bytes(const tpq_layout *L)
 {
     if (check_layout(L) != TPQ_OK) return 0;
-    const size_t n = static_cast<size_t>(plan_offsets(L->k, L->r).total);
+    const size_t n = static_cast<size_t>(plan_offsets(L->k, L->r, L->G).total);
     return (n + 255) / 256 * 256;
 }
 

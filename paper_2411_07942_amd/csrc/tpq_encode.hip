@@ -1,6 +1,7 @@
 // tpq_encode kernels: the compression function C^(i) (paper Sec. 2) in the hybrid
 // form of Fig. 2 -- selected features verbatim in BF16, the rest as packed 4-bit
 // codes with a per-group bf16 scale and zero.
+#include <stdlib.h>
 #include "tpq_device.h"
 #include "tpq_internal.h"
 
@@ -129,27 +130,51 @@ __global__ __launch_bounds__(64) void k_encode_row(EncodeArgs a, RankPtrs Yp, Ra
 // ---------------------------------------------------------------------------
 // Streaming kernel (the fast path).
 //
-// A task is one segment of one row of one rank: P passes of 64 chunks.  Groups
+// Work unit: one segment (P passes of 64 chunks) of one row of one rank.  Groups
 // never straddle a pass (64 chunks = 512 features, a multiple of every G), so
-// segments are independent.  One wavefront per task, four tasks per workgroup,
-// no workgroup barrier: all LDS use is private to a wave.
+// segments are independent.  The grid is persistent: blockIdx.y = rank,
+// blockIdx.z = segment, and the 4 wavefronts of each of the gridDim.x workgroups
+// walk over the rows t = 4*blockIdx.x + wave, + 4*gridDim.x, ...  Each wave keeps
+// the next row's loads in flight while it works on the current one.
 //
-//   A. the columns of the row that the segment covers are fetched with aligned,
-//      coalesced 128-bit loads (all of a lane's loads in flight together) and
-//      parked in LDS;
-//   B. the few chunks that an outlier splits (at most k + 1 per row) are gathered
-//      element by element from LDS by as many lanes and parked in an LDS patch
-//      area; the selected columns themselves go to the outlier section;
-//   C. every lane reads its 8 consecutive compacted features with one 128-bit LDS
-//      read at the chunk's start column -- 2-byte aligned, since removing the
-//      selected columns shifts the compacted stream by their count; owners of
+// LDS stage of a wave.  The row slice is kept as 32-bit words in blocks of
+// 32 words (8 aligned 16-byte chunks) that occupy 37 words each: the 32 words,
+// a copy of the next block's first 4 words, and one pad word.  A lane reads the
+// 5 words that hold its 8 consecutive compacted features starting at any word;
+// the copy keeps those 5 words contiguous and the odd block stride spreads the
+// 64 lanes (16 bytes apart) over all banks.  Every LDS access is word aligned:
+// removing the selected columns shifts the compacted stream by their count, so a
+// chunk starts at any 2-byte boundary, and the remaining half-word shift is one
+// funnel shift per word in registers.
+//
+// Once per workgroup: per-chunk stage addresses go to registers; the stage
+// addresses of the split chunks' sources and of the selected columns go to LDS.
+// Per row:
+//   A. the row slice arrives through aligned, coalesced 128-bit loads issued one
+//      row ahead, is written to the stage, and the next row's loads are issued;
+//   B. the few chunks that an outlier splits (at most k + 1 per row, plus the
+//      absent tail of the last group) are gathered half-word by half-word from the
+//      stage by as many lanes into a patch area; the selected columns are copied
+//      from the stage to the outlier section;
+//   C. every lane fetches its 8 features (5 words + funnel shift); owners of
 //      split chunks take theirs from the patch area;
-//   D. lane-local min / max of 8 features, DPP reduction over the group's lanes,
-//      leaders park (min, max) in LDS;
+//   D. lane-local min / max, DPP reduction over the group's lanes, leaders park
+//      (min, max) in LDS;
 //   E. one lane per group derives zero, bf16 scale and reciprocal (two IEEE
 //      divisions per group instead of per lane) and stores scale / zero;
 //   F. quantise from registers, pack 8 nibbles per lane, coalesced store.
+// No workgroup barrier inside the row loop: stage, patch and meta are private to
+// a wave.
 // ---------------------------------------------------------------------------
+constexpr uint32_t kStageBlockBytes = 37 * 4;
+
+// byte offset in the stage of the half-word at relative column c
+__device__ __forceinline__ uint32_t stage_addr(uint32_t c)
+{
+    const uint32_t word = c >> 1;
+    return 4u * (word + 5u * (word >> 5)) + 2u * (c & 1u);
+}
+
 template <int LPG, int P>
 __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp, RankPtrs codesp,
                                                        RankPtrs scalep, RankPtrs zerop,
@@ -158,12 +183,9 @@ __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp
     const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
     if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
         ph->G != a.G)
-        return;
+        return;  // the whole grid takes this branch together
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // grid: x = groups of 4 rows, y = rank, z = segment of the row
-    const uint32_t t = blockIdx.x * 4u + wave;
-    if (t >= static_cast<uint32_t>(a.T)) return;
     const uint32_t rank = blockIdx.y;
     const uint32_t seg = blockIdx.z;
 
@@ -171,7 +193,7 @@ __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp
     const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
     const uint16_t *pass_irr = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_irr_offset);
     const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_col_offset);
-    const u32x4 *irr_src = reinterpret_cast<const u32x4 *>(a.plan + ph->irr_src_offset);
+    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
 
     const uint32_t pass0 = seg * P;
     const uint32_t passes_total = static_cast<uint32_t>(a.chunks_padded) >> 6;
@@ -183,158 +205,216 @@ __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp
     const uint32_t col_lo = seg == 0 ? 0u : (c_first & ~7u);
     const uint32_t col_hi = last_seg ? static_cast<uint32_t>(a.E) : ((c_next + 7u) & ~7u);
     const uint32_t n16 = (col_hi - col_lo) >> 3;
-    // selected columns owned by this segment
+    // selected columns and split chunks owned by this segment
     const uint32_t p_lo = seg == 0 ? 0u : c_first - 512u * pass0;
     const uint32_t p_hi = last_seg ? static_cast<uint32_t>(a.k) : c_next - 512u * (pass0 + n_pass);
+    const uint32_t q_lo = pass_irr[pass0], q_hi = pass_irr[pass0 + n_pass];
+    const uint32_t n_q = q_hi - q_lo, n_sel = p_hi - p_lo;
 
+    constexpr int S = P + 1;           // staging loads per lane; 64*S >= n16 (host-checked)
     constexpr int GPS = 64 * P / LPG;  // groups per segment
-    constexpr int META16 = (GPS * 8 + 15) / 16;
+    constexpr uint32_t STAGE_BYTES = (8u * S * kStageBlockBytes + 15u) / 16u * 16u;
+    constexpr uint32_t META_BYTES = (GPS * 8u + 15u) / 16u * 16u;
     extern __shared__ u32x4 smem_stream[];
-    u32x4 *stage = smem_stream + wave * (a.stage_chunks + a.patch_slots + META16);
-    u32x4 *patch = stage + a.stage_chunks;
-    float2 *meta = reinterpret_cast<float2 *>(patch + a.patch_slots);
-    const uint16_t *stage16 = reinterpret_cast<const uint16_t *>(stage);
+    uint8_t *lds = reinterpret_cast<uint8_t *>(smem_stream);
+    // workgroup-wide tables, then one (stage | patch | meta) region per wave
+    uint16_t *l_irr = reinterpret_cast<uint16_t *>(lds);                       // [patch_slots][8]
+    uint16_t *l_sel = reinterpret_cast<uint16_t *>(lds + 16u * a.patch_slots);  // [k]
+    const uint32_t tables_bytes = 16u * a.patch_slots + ((2u * a.k + 15u) & ~15u);
+    const uint32_t wave_bytes = STAGE_BYTES + 16u * a.patch_slots + META_BYTES;
+    uint8_t *stage = lds + tables_bytes + wave * wave_bytes;
+    u32x4 *patch = reinterpret_cast<u32x4 *>(stage + STAGE_BYTES);
+    float2 *meta = reinterpret_cast<float2 *>(stage + STAGE_BYTES + 16u * a.patch_slots);
 
-    // A: the row slice -> LDS (index clamped instead of masked: no divergence)
-    {
-        const u32x4 *yrow = reinterpret_cast<const u32x4 *>(
-                                static_cast<const uint16_t *>(Yp.p[rank]) +
-                                static_cast<int64_t>(t) * a.ldY) + (col_lo >> 3);
-        constexpr int S = P + 1;
-        u32x4 rbuf[S];
-#pragma unroll
-        for (int j = 0; j < S; ++j) {
-            const uint32_t c = min(j * 64u + lane, n16 - 1u);
-            rbuf[j] = __builtin_nontemporal_load(yrow + c);
-        }
-#pragma unroll
-        for (int j = 0; j < S; ++j) {
-            const uint32_t c = min(j * 64u + lane, n16 - 1u);
-            stage[c] = rbuf[j];
-        }
-        for (uint32_t c = S * 64u + lane; c < n16; c += 64) stage[c] = yrow[c];
-    }
+    // tables -> LDS as stage byte offsets
+    for (uint32_t i = threadIdx.x; i < 8u * n_q; i += 256)
+        l_irr[i] = static_cast<uint16_t>(stage_addr(irr_src[8u * q_lo + i] - col_lo));
+    for (uint32_t i = threadIdx.x; i < n_sel; i += 256)
+        l_sel[i] = static_cast<uint16_t>(stage_addr(static_cast<uint32_t>(idx[p_lo + i]) - col_lo));
+    // per chunk: bits 15..0 = stage byte offset of the word holding its first feature,
+    // bits 20..16 = funnel shift (16 if that feature is the word's upper half),
+    // bits 30..21 = patch slot within the segment (kSlotNone: none), bit 31 = take
+    // the features from the patch area
+    constexpr uint32_t kSlotNone = 0x3FFu;
     uint32_t cp[P];
 #pragma unroll
-    for (int p = 0; p < P; ++p)
-        cp[p] = static_cast<uint32_t>(p) < n_pass
-                    ? cpos[(pass0 + p) * 64u + lane]
-                    : (kNotRegular | (kNoSlot << 16) | (col_hi - 8u));
-    const uint32_t q_lo = pass_irr[pass0], q_hi = pass_irr[pass0 + n_pass];
-    wave_lds_fence();
-
-    // B: split chunks of this segment -> patch area; selected columns -> outlier section
-    for (uint32_t q = q_lo + lane; q < q_hi; q += 64) {
-        const u32x4 tab = irr_src[q];
-        u32x4 g;
-        g.x = stage16[(tab.x & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.x >> 16) - col_lo]) << 16);
-        g.y = stage16[(tab.y & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.y >> 16) - col_lo]) << 16);
-        g.z = stage16[(tab.z & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.z >> 16) - col_lo]) << 16);
-        g.w = stage16[(tab.w & 0xFFFFu) - col_lo] | (static_cast<uint32_t>(stage16[(tab.w >> 16) - col_lo]) << 16);
-        patch[q - q_lo] = g;
-    }
-    if (p_lo < p_hi) {
-        uint16_t *outl = reinterpret_cast<uint16_t *>(
-            static_cast<uint8_t *>(const_cast<void *>(outlp.p[rank])) +
-            static_cast<int64_t>(t) * a.pitch_outl);
-        for (uint32_t p = p_lo + lane; p < p_hi; p += 64) outl[p] = stage16[idx[p] - col_lo];
-    }
-
-    // C: 8 consecutive compacted features per lane and pass
-    u32x4 v[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-        v[p] = *reinterpret_cast<const u32x4_a2 *>(stage16 + ((cp[p] & 0xFFFFu) - col_lo));
-    wave_lds_fence();
-#pragma unroll
     for (int p = 0; p < P; ++p) {
-        const uint32_t slot = (cp[p] >> 16) & 0x7FFFu;
-        if ((cp[p] & kNotRegular) && slot != kNoSlot) v[p] = patch[slot - q_lo];
+        const uint32_t c = static_cast<uint32_t>(p) < n_pass
+                               ? cpos[(pass0 + p) * 64u + lane]
+                               : (kNotRegular | (kNoSlot << 16) | (col_hi - 8u));
+        const uint32_t col = (c & 0xFFFFu) - col_lo;
+        const uint32_t slot = (c >> 16) & 0x7FFFu;
+        const bool patched = (c & kNotRegular) && slot != kNoSlot;
+        cp[p] = (stage_addr(col) & ~3u) | ((col & 1u) << 20) |
+                ((patched ? slot - q_lo : kSlotNone) << 21) | (patched ? kNotRegular : 0u);
+    }
+    __syncthreads();
+
+    const uint32_t t0 = blockIdx.x * 4u + wave, t_step = gridDim.x * 4u;
+    const uint32_t T = static_cast<uint32_t>(a.T);
+    const uint16_t *ybase = static_cast<const uint16_t *>(Yp.p[rank]) + col_lo;
+    u32x4 rbuf[S];
+    if (t0 < T) {
+        const u32x4 *yrow = reinterpret_cast<const u32x4 *>(ybase + static_cast<int64_t>(t0) * a.ldY);
+#pragma unroll
+        for (int j = 0; j < S; ++j)
+            rbuf[j] = __builtin_nontemporal_load(yrow + min(j * 64u + lane, n16 - 1u));
     }
 
-    // D: group min / max
-    {
-        float mn[P], mx[P];
+    for (uint32_t t = t0; t < T; t += t_step) {
+        // Re-derive every per-lane address inside the iteration: hoisted out of the
+        // loop they would cost more registers than the few instructions they save.
+        uint32_t ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int p = 0; p < P; ++p) asm volatile("" : "+v"(cp[p]));
+
+        // A: current row -> stage (chunk 64*j + ln: block 8*j + ln/8, slot ln%8; the
+        // first chunk of a block is also copied behind the previous block), then the
+        // next row's loads -> flight
+        {
+            uint8_t *w = stage + kStageBlockBytes * (ln >> 3) + 16u * (ln & 7u);
+            const bool first_of_block = (ln & 7u) == 0;
+#pragma unroll
+            for (int j = 0; j < S; ++j) {
+                *reinterpret_cast<u32x4_a4 *>(w + j * 8 * kStageBlockBytes) = rbuf[j];
+                if (first_of_block && (j > 0 || ln >= 8))
+                    *reinterpret_cast<u32x4_a4 *>(w + j * 8 * kStageBlockBytes - 20) = rbuf[j];
+            }
+        }
+        if (t + t_step < T) {
+            const u32x4 *yrow = reinterpret_cast<const u32x4 *>(
+                ybase + static_cast<int64_t>(t + t_step) * a.ldY);
+#pragma unroll
+            for (int j = 0; j < S; ++j)
+                rbuf[j] = __builtin_nontemporal_load(yrow + min(j * 64u + ln, n16 - 1u));
+        }
+        wave_lds_fence();
+
+        // B: split chunks -> patch area; selected columns -> outlier section
+        for (uint32_t q = ln; q < n_q; q += 64) {
+            const u32x4 tab = *reinterpret_cast<const u32x4 *>(l_irr + 8u * q);
+            u32x4 g;
+#define TPQ_HW(off) static_cast<uint32_t>(*reinterpret_cast<const uint16_t *>(stage + (off)))
+            g.x = TPQ_HW(tab.x & 0xFFFFu) | (TPQ_HW(tab.x >> 16) << 16);
+            g.y = TPQ_HW(tab.y & 0xFFFFu) | (TPQ_HW(tab.y >> 16) << 16);
+            g.z = TPQ_HW(tab.z & 0xFFFFu) | (TPQ_HW(tab.z >> 16) << 16);
+            g.w = TPQ_HW(tab.w & 0xFFFFu) | (TPQ_HW(tab.w >> 16) << 16);
+            patch[q] = g;
+        }
+        if (n_sel > 0) {
+            uint16_t *outl = reinterpret_cast<uint16_t *>(
+                                 static_cast<uint8_t *>(const_cast<void *>(outlp.p[rank])) +
+                                 static_cast<int64_t>(t) * a.pitch_outl) + p_lo;
+            for (uint32_t p = ln; p < n_sel; p += 64) outl[p] = static_cast<uint16_t>(TPQ_HW(l_sel[p]));
+        }
+#undef TPQ_HW
+
+        // C: 8 consecutive compacted features per lane and pass
+        u32x4 v[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const float a0 = bf16_lo_to_f32(v[p].x), a1 = bf16_hi_to_f32(v[p].x);
-            const float a2 = bf16_lo_to_f32(v[p].y), a3 = bf16_hi_to_f32(v[p].y);
-            const float a4 = bf16_lo_to_f32(v[p].z), a5 = bf16_hi_to_f32(v[p].z);
-            const float a6 = bf16_lo_to_f32(v[p].w), a7 = bf16_hi_to_f32(v[p].w);
-            mn[p] = fminf(fminf(fminf(a0, a1), fminf(a2, a3)), fminf(fminf(a4, a5), fminf(a6, a7)));
-            mx[p] = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), fmaxf(fmaxf(a4, a5), fmaxf(a6, a7)));
-            if ((cp[p] >> 16) == (0x8000u | kNoSlot)) {  // beyond the row: neutral
-                mn[p] = 3.4028235e38f;
-                mx[p] = -3.4028235e38f;
-            }
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(stage + (cp[p] & 0xFFFFu));
+            const uint32_t d0 = src[0], d1 = src[1], d2 = src[2], d3 = src[3], d4 = src[4];
+            const uint32_t sh = (cp[p] >> 16) & 31u;
+            v[p].x = __builtin_amdgcn_alignbit(d1, d0, sh);
+            v[p].y = __builtin_amdgcn_alignbit(d2, d1, sh);
+            v[p].z = __builtin_amdgcn_alignbit(d3, d2, sh);
+            v[p].w = __builtin_amdgcn_alignbit(d4, d3, sh);
         }
-        group_minmax_n<LPG, P>(mn, mx);
-        if ((lane % LPG) == 0) {
+        wave_lds_fence();
 #pragma unroll
-            for (int p = 0; p < P; ++p) meta[(p * 64 + lane) / LPG] = make_float2(mn[p], mx[p]);
-        }
-    }
-    wave_lds_fence();
+        for (int p = 0; p < P; ++p)
+            if (cp[p] & kNotRegular) v[p] = patch[(cp[p] >> 21) & 0x3FFu];
 
-    // E: zero, scale, reciprocal -- one lane per group
-    {
-        uint16_t *scale = reinterpret_cast<uint16_t *>(
-            static_cast<uint8_t *>(const_cast<void *>(scalep.p[rank])) +
-            static_cast<int64_t>(t) * a.pitch_meta);
-        uint16_t *zero = reinterpret_cast<uint16_t *>(
-            static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
-            static_cast<int64_t>(t) * a.pitch_meta);
-        const uint32_t g0 = pass0 * (64 / LPG);
-        for (uint32_t gl = lane; gl < static_cast<uint32_t>(GPS); gl += 64) {
-            const uint32_t g = g0 + gl;
-            if (g < static_cast<uint32_t>(a.ng)) {
-                const float2 mm = meta[gl];
-                const float mn = mm.x + 0.0f;  // a zero minimum is stored as +0
-                const float span = mm.y - mn;
-                const float s32 = span / 15.0f;
-                const uint32_t sb = f32_to_bf16_bits(s32);
-                const float s = bf16_bits_to_f32(sb);
-                const bool constant = s < 1e-30f;
-                const float inv = constant ? 0.0f : 1.0f / s;
-                scale[g] = constant ? uint16_t(0) : static_cast<uint16_t>(sb);
-                zero[g] = static_cast<uint16_t>(__float_as_uint(mn) >> 16);
-                meta[gl] = make_float2(mn, inv);
+        // D: group min / max.  The upper feature of a word is compared as the whole
+        // word: as a float the word lies between that feature and its successor in
+        // magnitude, so it wins exactly where the feature would, and masking the
+        // winner's low half gives the feature itself.
+        {
+            float mn[P], mx[P];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const float l0 = bf16_lo_to_f32(v[p].x), l1 = bf16_lo_to_f32(v[p].y);
+                const float l2 = bf16_lo_to_f32(v[p].z), l3 = bf16_lo_to_f32(v[p].w);
+                const float h0 = __uint_as_float(v[p].x), h1 = __uint_as_float(v[p].y);
+                const float h2 = __uint_as_float(v[p].z), h3 = __uint_as_float(v[p].w);
+                const float lo = fminf(fminf(fminf(l0, l1), fminf(l2, l3)),
+                                       fminf(fminf(h0, h1), fminf(h2, h3)));
+                const float hi = fmaxf(fmaxf(fmaxf(l0, l1), fmaxf(l2, l3)),
+                                       fmaxf(fmaxf(h0, h1), fmaxf(h2, h3)));
+                mn[p] = __uint_as_float(__float_as_uint(lo) & 0xFFFF0000u);
+                mx[p] = __uint_as_float(__float_as_uint(hi) & 0xFFFF0000u);
+            }
+            group_minmax_n<LPG, P>(mn, mx);
+            if ((ln % LPG) == 0) {
+#pragma unroll
+                for (int p = 0; p < P; ++p) meta[(p * 64 + ln) / LPG] = make_float2(mn[p], mx[p]);
             }
         }
-    }
-    wave_lds_fence();
+        wave_lds_fence();
 
-    // F: quantise and pack.  (x - zero) * inv lies in [0, 15.06] for finite input
-    // (scale is (max - min) / 15 rounded to 8 significant bits), so the rounded
-    // value needs no clamp to stay a 4-bit code.
-    uint32_t *codes = reinterpret_cast<uint32_t *>(
-        static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
-        static_cast<int64_t>(t) * a.pitch_codes);
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const uint32_t chunk = (pass0 + p) * 64u + lane;
-        const float2 mi = meta[(p * 64 + lane) / LPG];
-        const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
-        float h[2];
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            float q[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t word = wv[half * 2 + (e >> 1)];
-                const float x = (e & 1) ? bf16_hi_to_f32(word) : bf16_lo_to_f32(word);
-                const float d = x - mi.x;
-                const float pr = d * mi.y;
-                q[e] = rintf(pr);
+        // E: zero, scale, reciprocal -- one lane per group
+        {
+            uint16_t *scale = reinterpret_cast<uint16_t *>(
+                static_cast<uint8_t *>(const_cast<void *>(scalep.p[rank])) +
+                static_cast<int64_t>(t) * a.pitch_meta);
+            uint16_t *zero = reinterpret_cast<uint16_t *>(
+                static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
+                static_cast<int64_t>(t) * a.pitch_meta);
+            const uint32_t g0 = pass0 * (64 / LPG);
+            for (uint32_t gl = ln; gl < static_cast<uint32_t>(GPS); gl += 64) {
+                const uint32_t g = g0 + gl;
+                if (g < static_cast<uint32_t>(a.ng)) {
+                    const float2 mm = meta[gl];
+                    const float mn = mm.x + 0.0f;  // a zero minimum is stored as +0
+                    const float span = mm.y - mn;
+                    const float s32 = span / 15.0f;
+                    const uint32_t sb = f32_to_bf16_bits(s32);
+                    const float s = bf16_bits_to_f32(sb);
+                    const bool constant = s < 1e-30f;
+                    const float inv = constant ? 0.0f : 1.0f / s;
+                    scale[g] = constant ? uint16_t(0) : static_cast<uint16_t>(sb);
+                    zero[g] = static_cast<uint16_t>(__float_as_uint(mn) >> 16);
+                    meta[gl] = make_float2(mn, inv);
+                }
             }
-            // four codes -> one 16-bit integer, exactly, in fp32
-            h[half] = __builtin_fmaf(q[3], 4096.0f,
-                                     __builtin_fmaf(q[2], 256.0f, __builtin_fmaf(q[1], 16.0f, q[0])));
         }
-        uint32_t w = static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16);
-        const int n_valid = a.r - 8 * static_cast<int>(chunk);
-        if (n_valid < 8) w &= (1u << (4 * (n_valid & 7))) - 1u;
-        if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w, codes + chunk);
+        wave_lds_fence();
+
+        // F: quantise and pack.  (x - zero) * inv lies in [0, 15.06] for finite input
+        // (scale is (max - min) / 15 rounded to 8 significant bits), so the rounded
+        // value needs no clamp to stay a 4-bit code.
+        uint32_t *codes = reinterpret_cast<uint32_t *>(
+            static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
+            static_cast<int64_t>(t) * a.pitch_codes);
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t chunk = (pass0 + p) * 64u + ln;
+            const float2 mi = meta[(p * 64 + ln) / LPG];
+            const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+            float h[2];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float q[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t word = wv[half * 2 + (e >> 1)];
+                    const float x = (e & 1) ? bf16_hi_to_f32(word) : bf16_lo_to_f32(word);
+                    const float d = x - mi.x;
+                    const float pr = d * mi.y;
+                    q[e] = rintf(pr);
+                }
+                // four codes -> one 16-bit integer, exactly, in fp32
+                h[half] = __builtin_fmaf(q[3], 4096.0f,
+                                         __builtin_fmaf(q[2], 256.0f, __builtin_fmaf(q[1], 16.0f, q[0])));
+            }
+            uint32_t w = static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16);
+            const int n_valid = a.r - 8 * static_cast<int>(chunk);
+            if (n_valid < 8) w &= (1u << (4 * (n_valid & 7))) - 1u;
+            if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w, codes + chunk);
+        }
+        wave_lds_fence();  // the next row overwrites stage / patch / meta
     }
 }
 
@@ -363,13 +443,16 @@ static int pick_seg_passes(int passes, int *segs)
 template <int LPG>
 static hipError_t launch_stream_lpg(EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                                     const RankPtrs &scale, const RankPtrs &zero,
-                                    const RankPtrs &outl, hipStream_t s)
+                                    const RankPtrs &outl, int blocks_x, hipStream_t s)
 {
     const int P = a.seg_passes;
-    const size_t meta16 = (static_cast<size_t>(64 * P / LPG) * 8 + 15) / 16;
-    const size_t lds = 4 * 16 * (static_cast<size_t>(a.stage_chunks) + a.patch_slots + meta16);
+    const size_t meta_bytes = (static_cast<size_t>(64 * P / LPG) * 8 + 15) / 16 * 16;
+    const size_t stage_bytes = (static_cast<size_t>(8) * (P + 1) * 37 * 4 + 15) / 16 * 16;
+    const size_t per_wave = stage_bytes + 16u * a.patch_slots + meta_bytes;
+    const size_t tables = 16u * a.patch_slots + ((2u * a.k + 15u) & ~static_cast<size_t>(15));
+    const size_t lds = tables + 4 * per_wave;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<unsigned>((a.T + 3) / 4), static_cast<unsigned>(a.n_ranks),
+    const dim3 grid(static_cast<unsigned>(blocks_x), static_cast<unsigned>(a.n_ranks),
                     static_cast<unsigned>(a.segs));
     hipError_t e = hipSuccess;
 #define TPQ_CASE(PP)                                                                         \
@@ -399,11 +482,15 @@ int launch_encode(const EncodeArgs &a_in, const RankPtrs &Y, const RankPtrs &cod
     const int lpg = a.G / 8;
     hipError_t e = hipSuccess;
 
-    // Streaming path: needs at least one quantised feature and an LDS patch area
-    // (k + 1 slots of 16 bytes per wave) of moderate size.
-    const int slots = irr_slots_of(a.k, a.r);
-    if (a.r > 0 && slots <= 512) {
+    // Streaming path: needs at least one quantised feature, an LDS patch area (k + 1
+    // slots of 16 bytes per wave) of moderate size and a shift of at most 62 chunks.
+    const int slots = irr_slots_of(a.k, a.r, a.G);
+    if (a.r > 0 && slots <= 1000 && (a.k + 7) / 8 + 2 <= 64) {
         a.seg_passes = pick_seg_passes(a.chunks_padded / 64, &a.segs);
+        if (const char *ev = getenv("TPQ_DEBUG_SEG_PASSES")) {  // EXPERIMENT ONLY
+            a.seg_passes = atoi(ev);
+            a.segs = (a.chunks_padded / 64 + a.seg_passes - 1) / a.seg_passes;
+        }
         a.patch_slots = slots;
         // a segment's slice: its 64*P chunks, shifted by at most k columns, plus rounding
         {
@@ -412,11 +499,19 @@ int launch_encode(const EncodeArgs &a_in, const RankPtrs &Y, const RankPtrs &cod
             a.stage_chunks = need < whole ? need : whole;
         }
         a.n_tasks = a.T * a.n_ranks * a.segs;
+        // persistent grid: about 8 waves per CU over the whole launch, never more
+        // workgroups than there are groups of 4 rows
+        int wg_per_cu = 2;
+        if (const char *ev = getenv("TPQ_DEBUG_WG_PER_CU")) wg_per_cu = atoi(ev);  // EXPERIMENT ONLY
+        int64_t blocks_x = (256LL * wg_per_cu + a.n_ranks * a.segs - 1) / (a.n_ranks * a.segs);
+        const int64_t row_groups = (a.T + 3) / 4;
+        if (blocks_x > row_groups) blocks_x = row_groups;
+        if (blocks_x < 1) blocks_x = 1;
         switch (lpg) {
-        case 4: e = launch_stream_lpg<4>(a, Y, codes, scale, zero, outl, s); break;
-        case 8: e = launch_stream_lpg<8>(a, Y, codes, scale, zero, outl, s); break;
-        case 16: e = launch_stream_lpg<16>(a, Y, codes, scale, zero, outl, s); break;
-        case 32: e = launch_stream_lpg<32>(a, Y, codes, scale, zero, outl, s); break;
+        case 4: e = launch_stream_lpg<4>(a, Y, codes, scale, zero, outl, (int)blocks_x, s); break;
+        case 8: e = launch_stream_lpg<8>(a, Y, codes, scale, zero, outl, (int)blocks_x, s); break;
+        case 16: e = launch_stream_lpg<16>(a, Y, codes, scale, zero, outl, (int)blocks_x, s); break;
+        case 32: e = launch_stream_lpg<32>(a, Y, codes, scale, zero, outl, (int)blocks_x, s); break;
         default: return TPQ_ERR_UNSUPPORTED;
         }
         return hip_result(e);

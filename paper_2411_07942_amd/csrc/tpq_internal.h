@@ -28,10 +28,13 @@ namespace tpq {
 //                                       an outlier splits the chunk or it is the
 //                                       ragged last one ("irregular"; bits 30..16 =
 //                                       its slot q in irr / irr_src), or the chunk
-//                                       lies beyond the row (slot = kNoSlot).
+//                                       lies beyond the row: if it shares the last
+//                                       real group it has a slot too (its 8 sources
+//                                       repeat the last feature, neutral for the
+//                                       group's min / max), else slot = kNoSlot.
 //   flags    uint16[chunks_padded]      scratch of the build (1 = irregular)
 //   irr      uint16[chunks_padded]      irr[q] = chunk number of the q-th irregular
-//                                       chunk, ascending; at most k + 1 of them
+//                                       chunk, ascending
 //   pass_irr uint16[passes + 1]         irregular chunks below pass p
 //   irr_src  uint16[8 * slots]          the 8 feature indices of irregular chunk q
 //   pass_col uint16[passes + 1]         column of the first feature of pass p
@@ -60,23 +63,25 @@ struct PlanHeader {
 };
 static_assert(sizeof(PlanHeader) == 64, "plan header is 64 bytes");
 
-inline int chunks_of(int r) { return (r + 7) / 8; }
-inline int chunks_padded_of(int r) { return (chunks_of(r) + 63) / 64 * 64; }
-inline int idx_bytes_of(int k) { return ((k + 3) / 4 * 4) * 4; }
+__host__ __device__ inline int chunks_of(int r) { return (r + 7) / 8; }
+__host__ __device__ inline int chunks_padded_of(int r) { return (chunks_of(r) + 63) / 64 * 64; }
+__host__ __device__ inline int idx_bytes_of(int k) { return ((k + 3) / 4 * 4) * 4; }
 
 // an upper bound of the irregular chunks of a row that the host can compute
-inline int irr_slots_of(int k, int r)
+__host__ __device__ inline int irr_slots_of(int k, int r, int G)
 {
+    // chunks split by an outlier or ragged (at most k + 1, and no more than there are
+    // chunks), plus the absent chunks that share the last real group (fewer than G / 8)
     const int c = chunks_of(r);
-    return k + 1 < c ? k + 1 : c;
+    return (k + 1 < c ? k + 1 : c) + G / 8 - 1;
 }
 
-inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
+__host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
 
 struct PlanOffsets {
     int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src, total;
 };
-inline PlanOffsets plan_offsets(int k, int r)
+__host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
 {
     const int cp = chunks_padded_of(r);
     PlanOffsets o;
@@ -88,7 +93,7 @@ inline PlanOffsets plan_offsets(int k, int r)
     o.pass_irr = o.irr + 2 * cp;
     o.pass_col = o.pass_irr + pass_tab_bytes_of(r);
     o.irr_src = o.pass_col + pass_tab_bytes_of(r);
-    o.total = o.irr_src + 16 * irr_slots_of(k, r);
+    o.total = o.irr_src + 16 * irr_slots_of(k, r, G);
     return o;
 }
 

@@ -75,7 +75,8 @@ __global__ void k_plan_pad(uint8_t *plan, int r, int chunks_padded, PlanOffsets 
 
 // flags[c] = 1 if chunk c cannot be served by one 16-byte access: an outlier sits
 // between its first and last feature, or it is the ragged last chunk.
-__global__ void k_plan_flags(uint8_t *plan, int r, int chunks, int chunks_padded, PlanOffsets o)
+__global__ void k_plan_flags(uint8_t *plan, int r, int chunks, int chunks_padded, int lpg,
+                             PlanOffsets o)
 {
     const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
     const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
@@ -83,9 +84,15 @@ __global__ void k_plan_flags(uint8_t *plan, int r, int chunks, int chunks_padded
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= chunks_padded) return;
     uint16_t f = 0;
-    if (c < chunks && h->status == kPlanOk) {
-        const bool ragged = 8 * c + 8 > r;
-        f = (ragged || src[8 * c + 7] - src[8 * c] != 7) ? 1 : 0;
+    if (h->status == kPlanOk && chunks > 0) {
+        if (c < chunks) {
+            const bool ragged = 8 * c + 8 > r;
+            f = (ragged || src[8 * c + 7] - src[8 * c] != 7) ? 1 : 0;
+        } else {
+            // beyond the row but inside the last real group: gets a slot whose sources
+            // all repeat the last feature
+            f = (c / lpg == (chunks - 1) / lpg) ? 1 : 0;
+        }
     }
     flags[c] = f;
 }
@@ -117,7 +124,7 @@ __global__ void k_plan_slots(uint8_t *plan, int E, int chunks, int chunks_padded
         pass_irr[c / 64] = static_cast<uint16_t>(q);
         pass_col[c / 64] = c < chunks ? src[8 * c] : static_cast<uint16_t>(E);
     }
-    if (c >= chunks || h->status != kPlanOk) {
+    if (h->status != kPlanOk || (c >= chunks && !flags[c])) {
         cpos[c] = kNotRegular | (kNoSlot << 16) | static_cast<uint32_t>(E - 8);
     } else if (flags[c] && q < slots) {
         int safe = src[8 * c];
@@ -126,7 +133,8 @@ __global__ void k_plan_slots(uint8_t *plan, int E, int chunks, int chunks_padded
         irr[q] = static_cast<uint16_t>(c);
         for (int e = 0; e < 8; ++e) irr_src[8 * q + e] = src[8 * c + e];
     } else {
-        cpos[c] = src[8 * c];
+        cpos[c] = c < chunks ? src[8 * c]
+                             : (kNotRegular | (kNoSlot << 16) | static_cast<uint32_t>(E - 8));
     }
 }
 
@@ -134,14 +142,14 @@ int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipSt
 {
     const int E = L->E, k = L->k, r = L->r;
     const int chunks = chunks_of(r), cp = chunks_padded_of(r);
-    const PlanOffsets o = plan_offsets(k, r);
+    const PlanOffsets o = plan_offsets(k, r, L->G);
     uint8_t *p = static_cast<uint8_t *>(plan);
     k_plan_init<<<1, 64, 0, s>>>(p, E, k, L->G, r, chunks, cp, o);
     k_plan_build<<<(E + 255) / 256, 256, 0, s>>>(p, idx, E, k, r, o);
     const int tail = 8 * cp - r;
     if (r > 0 && tail > 0) k_plan_pad<<<(tail + 255) / 256, 256, 0, s>>>(p, r, cp, o);
-    if (cp > 0) k_plan_flags<<<(cp + 255) / 256, 256, 0, s>>>(p, r, chunks, cp, o);
-    k_plan_slots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, chunks, cp, irr_slots_of(k, r), o);
+    if (cp > 0) k_plan_flags<<<(cp + 255) / 256, 256, 0, s>>>(p, r, chunks, cp, L->G / 8, o);
+    k_plan_slots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, chunks, cp, irr_slots_of(k, r, L->G), o);
     return hip_result(hipGetLastError());
 }
 
