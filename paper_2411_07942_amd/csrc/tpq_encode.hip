@@ -1,7 +1,6 @@
 // tpq_encode kernels: the compression function C^(i) (paper Sec. 2) in the hybrid
 // form of Fig. 2 -- selected features verbatim in BF16, the rest as packed 4-bit
 // codes with a per-group bf16 scale and zero.
-#include <stdlib.h>
 #include "tpq_device.h"
 #include "tpq_internal.h"
 
@@ -180,38 +179,57 @@ __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp
                                                        RankPtrs scalep, RankPtrs zerop,
                                                        RankPtrs outlp)
 {
-    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
-    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
-        ph->G != a.G)
-        return;  // the whole grid takes this branch together
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t rank = blockIdx.y;
     const uint32_t seg = blockIdx.z;
-
-    const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
-    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
-    const uint16_t *pass_irr = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_irr_offset);
-    const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_col_offset);
-    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
 
     const uint32_t pass0 = seg * P;
     const uint32_t passes_total = static_cast<uint32_t>(a.chunks_padded) >> 6;
     const uint32_t n_pass = passes_total - pass0 < P ? passes_total - pass0 : P;
     const bool last_seg = pass0 + n_pass == passes_total;
 
-    // columns [col_lo, col_hi) of the row are staged; both are multiples of 8
-    const uint32_t c_first = pass_col[pass0], c_next = pass_col[pass0 + n_pass];
-    const uint32_t col_lo = seg == 0 ? 0u : (c_first & ~7u);
-    const uint32_t col_hi = last_seg ? static_cast<uint32_t>(a.E) : ((c_next + 7u) & ~7u);
+    // Columns [col_lo, col_hi) of the row are staged; both are multiples of 8.  The
+    // first compacted feature of pass p sits at column 512*p + (selected columns
+    // before it), so the segment lies inside [512*pass0, 512*(pass0 + n_pass) + k]:
+    // bounds that need nothing from the plan, so the first row's loads can leave
+    // before any table has arrived.
+    const uint32_t col_lo = 512u * pass0;
+    const uint32_t col_hi =
+        last_seg ? static_cast<uint32_t>(a.E)
+                 : min(static_cast<uint32_t>(a.E), (512u * (pass0 + n_pass) + a.k + 7u) & ~7u);
     const uint32_t n16 = (col_hi - col_lo) >> 3;
-    // selected columns and split chunks owned by this segment
+
+    const uint32_t t0 = blockIdx.x * 4u + wave, t_step = gridDim.x * 4u;
+    const uint32_t T = static_cast<uint32_t>(a.T);
+    const uint16_t *ybase = static_cast<const uint16_t *>(Yp.p[rank]) + col_lo;
+    constexpr int S = P + 1;  // staging loads per lane; 64*S >= n16 (checked by the host)
+    u32x4 rbuf[S];
+    if (t0 < T) {
+        const u32x4 *yrow = reinterpret_cast<const u32x4 *>(ybase + static_cast<int64_t>(t0) * a.ldY);
+#pragma unroll
+        for (int j = 0; j < S; ++j)
+            rbuf[j] = __builtin_nontemporal_load(yrow + min(j * 64u + lane, n16 - 1u));
+    }
+
+    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
+    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
+        ph->G != a.G)
+        return;  // the whole grid takes this branch together
+    const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
+    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
+    const uint16_t *pass_irr = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_irr_offset);
+    const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_col_offset);
+    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
+
+    // selected columns and split chunks owned by this segment: the selected columns
+    // below the next segment's first feature that no earlier segment owns
+    const uint32_t c_first = pass_col[pass0], c_next = pass_col[pass0 + n_pass];
     const uint32_t p_lo = seg == 0 ? 0u : c_first - 512u * pass0;
     const uint32_t p_hi = last_seg ? static_cast<uint32_t>(a.k) : c_next - 512u * (pass0 + n_pass);
     const uint32_t q_lo = pass_irr[pass0], q_hi = pass_irr[pass0 + n_pass];
     const uint32_t n_q = q_hi - q_lo, n_sel = p_hi - p_lo;
 
-    constexpr int S = P + 1;           // staging loads per lane; 64*S >= n16 (host-checked)
     constexpr int GPS = 64 * P / LPG;  // groups per segment
     constexpr uint32_t STAGE_BYTES = (8u * S * kStageBlockBytes + 15u) / 16u * 16u;
     constexpr uint32_t META_BYTES = (GPS * 8u + 15u) / 16u * 16u;
@@ -249,17 +267,6 @@ __global__ __launch_bounds__(256) void k_encode_stream(EncodeArgs a, RankPtrs Yp
                 ((patched ? slot - q_lo : kSlotNone) << 21) | (patched ? kNotRegular : 0u);
     }
     __syncthreads();
-
-    const uint32_t t0 = blockIdx.x * 4u + wave, t_step = gridDim.x * 4u;
-    const uint32_t T = static_cast<uint32_t>(a.T);
-    const uint16_t *ybase = static_cast<const uint16_t *>(Yp.p[rank]) + col_lo;
-    u32x4 rbuf[S];
-    if (t0 < T) {
-        const u32x4 *yrow = reinterpret_cast<const u32x4 *>(ybase + static_cast<int64_t>(t0) * a.ldY);
-#pragma unroll
-        for (int j = 0; j < S; ++j)
-            rbuf[j] = __builtin_nontemporal_load(yrow + min(j * 64u + lane, n16 - 1u));
-    }
 
     for (uint32_t t = t0; t < T; t += t_step) {
         // Re-derive every per-lane address inside the iteration: hoisted out of the
@@ -425,19 +432,14 @@ static size_t encode_row_lds(const EncodeArgs &a, int lpg)
     return static_cast<size_t>(a.E) * 2 + (meta + 15) / 16 * 16;
 }
 
-// Passes per segment the streaming kernel is compiled for.
+// Passes per segment: rows are cut into segments of at most 6 passes (3072 features).
+// Short segments keep a wave's registers and LDS small, so that 16 waves fit on a CU.
 static int pick_seg_passes(int passes, int *segs)
 {
-    static const int kP[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
-    const int n_seg = (passes + 15) / 16;
-    const int need = (passes + n_seg - 1) / n_seg;
-    *segs = n_seg;
-    for (int p : kP)
-        if (p >= need) {
-            *segs = (passes + p - 1) / p;
-            return p;
-        }
-    return 16;
+    const int n_seg = (passes + 5) / 6;
+    const int p = (passes + n_seg - 1) / n_seg;
+    *segs = (passes + p - 1) / p;
+    return p;
 }
 
 template <int LPG>
@@ -465,8 +467,7 @@ static hipError_t launch_stream_lpg(EncodeArgs &a, const RankPtrs &Y, const Rank
             k_encode_stream<LPG, PP><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl); \
         break;
     switch (P) {
-        TPQ_CASE(1) TPQ_CASE(2) TPQ_CASE(3) TPQ_CASE(4) TPQ_CASE(5) TPQ_CASE(6) TPQ_CASE(8)
-        TPQ_CASE(10) TPQ_CASE(12) TPQ_CASE(16)
+        TPQ_CASE(1) TPQ_CASE(2) TPQ_CASE(3) TPQ_CASE(4) TPQ_CASE(5) TPQ_CASE(6)
     default: return hipErrorInvalidValue;
     }
 #undef TPQ_CASE
@@ -487,10 +488,6 @@ int launch_encode(const EncodeArgs &a_in, const RankPtrs &Y, const RankPtrs &cod
     const int slots = irr_slots_of(a.k, a.r, a.G);
     if (a.r > 0 && slots <= 1000 && (a.k + 7) / 8 + 2 <= 64) {
         a.seg_passes = pick_seg_passes(a.chunks_padded / 64, &a.segs);
-        if (const char *ev = getenv("TPQ_DEBUG_SEG_PASSES")) {  // EXPERIMENT ONLY
-            a.seg_passes = atoi(ev);
-            a.segs = (a.chunks_padded / 64 + a.seg_passes - 1) / a.seg_passes;
-        }
         a.patch_slots = slots;
         // a segment's slice: its 64*P chunks, shifted by at most k columns, plus rounding
         {
@@ -499,10 +496,9 @@ int launch_encode(const EncodeArgs &a_in, const RankPtrs &Y, const RankPtrs &cod
             a.stage_chunks = need < whole ? need : whole;
         }
         a.n_tasks = a.T * a.n_ranks * a.segs;
-        // persistent grid: about 8 waves per CU over the whole launch, never more
+        // persistent grid: about 16 waves per CU over the whole launch, never more
         // workgroups than there are groups of 4 rows
-        int wg_per_cu = 2;
-        if (const char *ev = getenv("TPQ_DEBUG_WG_PER_CU")) wg_per_cu = atoi(ev);  // EXPERIMENT ONLY
+        const int wg_per_cu = 4;
         int64_t blocks_x = (256LL * wg_per_cu + a.n_ranks * a.segs - 1) / (a.n_ranks * a.segs);
         const int64_t row_groups = (a.T + 3) / 4;
         if (blocks_x > row_groups) blocks_x = row_groups;
