@@ -28,6 +28,7 @@ __device__ __forceinline__ float round_to_bf16(float f)
 
 // 128-bit vector that the compiler may load / store as one instruction
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 // ... also at 2-byte alignment (gfx9 global memory accepts unaligned accesses in
 // the HSA configuration; the hardware splits an access that crosses a cache line)
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
