@@ -122,10 +122,6 @@ struct DecodeArgs {
     int64_t T, ldOut;
     int64_t pitch_codes, pitch_meta, pitch_outl;
     void *out;
-    int32_t lds_per_wave;     // bytes of LDS one wave owns
-    int32_t waves_per_block;  // rows per workgroup (1..4)
-    int32_t meta_in_lds;      // scales and zeros are parked in LDS (else read per use)
-    int32_t reserved;
 };
 
 // ---- host-side helpers --------------------------------------------------------
