@@ -1,6 +1,8 @@
 // tpq_decode_reduce kernel: dequantise the N devices' messages and add them
 // (paper Sec. 2, decompression D^(i) and the sum over devices; Fig. 2 caption),
 // selected features scattered back to their original columns.
+#include <type_traits>
+
 #include "tpq_device.h"
 #include "tpq_internal.h"
 
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
         const uint32_t p = (task - passes) * 64u + lane;
         if (p >= static_cast<uint32_t>(a.k)) return;
         const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
-        const int64_t off_outl = static_cast<int64_t>(t) * a.pitch_outl;
+        const uint32_t off_outl = t * static_cast<uint32_t>(a.pitch_outl);
         const uint32_t j = static_cast<uint32_t>(idx[p]);
         float acc = 0.f;
         for (uint32_t i0 = 0; i0 < N; i0 += 8) {
@@ -119,29 +121,35 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     // ---- one pass of quantised features ---------------------------------------------
     const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
     const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
-    const int64_t off_meta = static_cast<int64_t>(t) * a.pitch_meta;
-    const int64_t off_codes = static_cast<int64_t>(t) * a.pitch_codes;
     const uint32_t chunk = task * 64u + lane;
-    const uint32_t ld_chunk = min(chunk, chunks - 1u);
     const uint32_t g = min(chunk / LPG, ng - 1u);
+    // One 32-bit byte offset per section serves every rank (the host keeps
+    // T * pitch below 2^31 per launch): the rank only changes the scalar base.
+    const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
+    const uint32_t off_meta = t * static_cast<uint32_t>(a.pitch_meta) + 2u * g;
     const uint32_t cp = cpos[chunk];
     float acc[8];
-    for (uint32_t i0 = 0; i0 < N; i0 += 8) {
+
+    // 8 ranks at a time: all 24 loads first, then the arithmetic.  FULL batches index
+    // the pointer tables with constants (one wide scalar load each); the last, partial
+    // batch guards every rank.
+    auto batch = [&](uint32_t i0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
         uint32_t w[8], sb[8], zb[8];
+        const void *const *pc = codesp.p + i0;
+        const void *const *ps = scalep.p + i0;
+        const void *const *pz = zerop.p + i0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint32_t i = min(i0 + j, N - 1u);
-            w[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(codesp.p[i]) +
-                                                   off_codes) + ld_chunk);
-            sb[j] = reinterpret_cast<const uint16_t *>(
-                static_cast<const uint8_t *>(scalep.p[i]) + off_meta)[g];
-            zb[j] = reinterpret_cast<const uint16_t *>(
-                static_cast<const uint8_t *>(zerop.p[i]) + off_meta)[g];
+            const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
+            w[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                static_cast<const uint8_t *>(pc[i]) + off_codes));
+            sb[j] = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(ps[i]) + off_meta);
+            zb[j] = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(pz[i]) + off_meta);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (i0 + j < N) {  // uniform
+            if (FULL || i0 + j < N) {  // uniform
                 const float sc = bf16_bits_to_f32(sb[j]), ze = bf16_bits_to_f32(zb[j]);
                 // one code per byte, so that each converts with a single byte-to-float
                 // instruction (the masks are hidden from the optimiser, which would
@@ -157,7 +165,10 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
                 accumulate8<ACC>(acc, x, i0 + j == 0);
             }
         }
-    }
+    };
+    uint32_t i0 = 0;
+    for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
+    if (i0 < N) batch(i0, std::false_type{});
     if (chunk >= chunks) return;
 
     uint32_t o[8];  // the 8 results as output words (bf16: two per word)
@@ -199,15 +210,35 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     }
 }
 
-int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
-                  const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
+int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPtrs &scale_in,
+                  const RankPtrs &zero_in, const RankPtrs &outl_in, int accum, int out_dtype,
                   hipStream_t s)
 {
-    const int lpg = a.G / 8;
-    const int tasks = a.chunks_padded / 64 + (a.k + 63) / 64;  // waves per row
+    const int lpg = a_in.G / 8;
+    const int tasks = a_in.chunks_padded / 64 + (a_in.k + 63) / 64;  // waves per row
     if (tasks == 0) return TPQ_OK;
-    const dim3 grid(static_cast<unsigned>(a.T), static_cast<unsigned>((tasks + 3) / 4));
+    // The kernel addresses a rank's sections with 32-bit byte offsets: rows are handed
+    // over in blocks whose sections stay below 2 GiB (one block unless T is huge).
+    int64_t max_pitch = a_in.pitch_codes;
+    if (a_in.pitch_meta > max_pitch) max_pitch = a_in.pitch_meta;
+    if (a_in.pitch_outl > max_pitch) max_pitch = a_in.pitch_outl;
+    int64_t rows_per_launch = max_pitch > 0 ? (0x7FFFFFFFLL / max_pitch) : a_in.T;
+    if (rows_per_launch > 0x7FFFFFFFLL) rows_per_launch = 0x7FFFFFFFLL;
+    if (rows_per_launch < 1) return TPQ_ERR_SHAPE;
+    const size_t ob = out_dtype == TPQ_OUT_FP32 ? 4 : 2;
     hipError_t e = hipSuccess;
+    for (int64_t row0 = 0; row0 < a_in.T && e == hipSuccess; row0 += rows_per_launch) {
+        DecodeArgs a = a_in;
+        RankPtrs codes = codes_in, scale = scale_in, zero = zero_in, outl = outl_in;
+        a.T = a_in.T - row0 < rows_per_launch ? a_in.T - row0 : rows_per_launch;
+        a.out = static_cast<uint8_t *>(a_in.out) + row0 * a_in.ldOut * ob;
+        for (int i = 0; i < a_in.n_ranks; ++i) {
+            if (codes.p[i]) codes.p[i] = static_cast<const uint8_t *>(codes.p[i]) + row0 * a_in.pitch_codes;
+            if (scale.p[i]) scale.p[i] = static_cast<const uint8_t *>(scale.p[i]) + row0 * a_in.pitch_meta;
+            if (zero.p[i]) zero.p[i] = static_cast<const uint8_t *>(zero.p[i]) + row0 * a_in.pitch_meta;
+            if (outl.p[i]) outl.p[i] = static_cast<const uint8_t *>(outl.p[i]) + row0 * a_in.pitch_outl;
+        }
+        const dim3 grid(static_cast<unsigned>(a.T), static_cast<unsigned>((tasks + 3) / 4));
 #define TPQ_LAUNCH3(LPG, ACC, OUT) \
     k_decode_pass<LPG, ACC, OUT><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl)
 #define TPQ_LAUNCH2(LPG)                                                                     \
@@ -221,17 +252,18 @@ int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &sc
         else                                                                                 \
             TPQ_LAUNCH3(LPG, TPQ_ACC_BF16, TPQ_OUT_FP32);                                    \
     } while (0)
-    switch (lpg) {
-    case 4: TPQ_LAUNCH2(4); break;
-    case 8: TPQ_LAUNCH2(8); break;
-    case 16: TPQ_LAUNCH2(16); break;
-    case 32: TPQ_LAUNCH2(32); break;
-    default: return TPQ_ERR_UNSUPPORTED;
-    }
+        switch (lpg) {
+        case 4: TPQ_LAUNCH2(4); break;
+        case 8: TPQ_LAUNCH2(8); break;
+        case 16: TPQ_LAUNCH2(16); break;
+        case 32: TPQ_LAUNCH2(32); break;
+        default: return TPQ_ERR_UNSUPPORTED;
+        }
 #undef TPQ_LAUNCH2
 #undef TPQ_LAUNCH3
-    if (e != hipSuccess) return hip_result(e);
-    return hip_result(hipGetLastError());
+        e = hipGetLastError();
+    }
+    return hip_result(e);
 }
 
 }  // namespace tpq
