@@ -8,25 +8,30 @@ namespace tpq {
 
 constexpr int kStripLanes = 64;        // lanes across columns; 8 columns per lane
 constexpr int kStripCols = 8 * kStripLanes;
-constexpr int kWavesPerBlock = 4;      // waves of a block share columns, split rows
+constexpr int kWavesPerBlock = 8;      // waves of a block share columns, split rows
+constexpr int kMaxParts = 64;          // row slices per sequence
+constexpr int kUnroll = 8;             // rows in flight per lane
 
 // How many row slices ("parts") a sequence of S rows is cut into.  Each
-// (column strip, part) is one workgroup; the count only depends on (S, E), so
-// the workspace size does too.
+// (column strip, part) is one workgroup; the count only depends on S, so the
+// workspace size (parts x 2 x E floats) does too.
 int calibrate_parts(int64_t S, int E)
 {
-    const int strips = (E + kStripCols - 1) / kStripCols;
-    int64_t target = (4096 + strips - 1) / strips;       // aim at ~4096 workgroups
-    int64_t max_parts = (S + 31) / 32;                   // at least 32 rows per part
-    if (max_parts < 1) max_parts = 1;
-    int64_t parts = target < max_parts ? target : max_parts;
+    (void)E;
+    // at least one row per wave and unrolled step where S allows, at most kMaxParts
+    int64_t parts = S / (kWavesPerBlock * kUnroll);
+    if (parts > kMaxParts) parts = kMaxParts;
     if (parts < 1) parts = 1;
     return static_cast<int>(parts);
 }
 
+typedef unsigned int u32x4_cal __attribute__((ext_vector_type(4)));
+
 // Column min / max over one slice of rows.  Lane l of every wave owns columns
 // 8*(64*blockIdx.x + l) .. +7 and keeps 8 running minima and maxima in registers;
-// the block's 4 waves take interleaved rows and are combined through LDS.
+// the block's waves take interleaved rows, kUnroll 128-bit loads in flight each,
+// and are combined through LDS.  The upper bf16 of a word is compared as the whole
+// word (it orders like the value itself; the low half is masked off at the end).
 // Partials go to ws as [part][0 = min, 1 = max][E].
 __global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax(
     const uint16_t *__restrict__ Y, int64_t S, int64_t ldY, int E, int rows_per_part,
@@ -47,21 +52,34 @@ __global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax(
         mx[e] = -3.4028235e38f;
     }
     if (live) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(Y + col8 * 8);
-        const int64_t stride = ldY / 8;  // in uint4
-#pragma unroll 4
-        for (int64_t t = row0 + wave; t < row1; t += kWavesPerBlock) {
-            const uint4 v = p[t * stride];
+        const u32x4_cal *p = reinterpret_cast<const u32x4_cal *>(Y + col8 * 8);
+        const int64_t stride = ldY / 8;  // in 16-byte units
+        auto fold = [&](const u32x4_cal &v) {
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float lo = bf16_lo_to_f32(w[e]);
-                const float hi = bf16_hi_to_f32(w[e]);
+                const float hi = __uint_as_float(w[e]);
                 mn[2 * e] = fminf(mn[2 * e], lo);
                 mx[2 * e] = fmaxf(mx[2 * e], lo);
                 mn[2 * e + 1] = fminf(mn[2 * e + 1], hi);
                 mx[2 * e + 1] = fmaxf(mx[2 * e + 1], hi);
             }
+        };
+        int64_t t = row0 + wave;
+        for (; t + (kUnroll - 1) * kWavesPerBlock < row1; t += kUnroll * kWavesPerBlock) {
+            u32x4_cal v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                v[u] = __builtin_nontemporal_load(p + (t + u * kWavesPerBlock) * stride);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) fold(v[u]);
+        }
+        for (; t < row1; t += kWavesPerBlock) fold(__builtin_nontemporal_load(p + t * stride));
+#pragma unroll
+        for (int e = 1; e < 8; e += 2) {
+            mn[e] = __uint_as_float(__float_as_uint(mn[e]) & 0xFFFF0000u);
+            mx[e] = __uint_as_float(__float_as_uint(mx[e]) & 0xFFFF0000u);
         }
     }
 
@@ -72,33 +90,45 @@ __global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax(
         red[wave][1][e][lane] = mx[e];
     }
     __syncthreads();
-    if (wave == 0 && live) {
-        float *out_mn = ws + (static_cast<int64_t>(blockIdx.y) * 2 + 0) * E + col8 * 8;
-        float *out_mx = ws + (static_cast<int64_t>(blockIdx.y) * 2 + 1) * E + col8 * 8;
+    // thread (wave, lane): feature 8*lane... each of the 8 waves finishes one of the 8
+    // features of every lane's column group
+    if (live) {
+        const int e = wave;
+        float a = red[0][0][e][lane], b = red[0][1][e][lane];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float a = red[0][0][e][lane], b = red[0][1][e][lane];
-#pragma unroll
-            for (int w2 = 1; w2 < kWavesPerBlock; ++w2) {
-                a = fminf(a, red[w2][0][e][lane]);
-                b = fmaxf(b, red[w2][1][e][lane]);
-            }
-            out_mn[e] = a;
-            out_mx[e] = b;
+        for (int w2 = 1; w2 < kWavesPerBlock; ++w2) {
+            a = fminf(a, red[w2][0][e][lane]);
+            b = fmaxf(b, red[w2][1][e][lane]);
         }
+        ws[(static_cast<int64_t>(blockIdx.y) * 2 + 0) * E + col8 * 8 + e] = a;
+        ws[(static_cast<int64_t>(blockIdx.y) * 2 + 1) * E + col8 * 8 + e] = b;
     }
 }
 
-// Combine the parts and apply Eq. (1), (2) to one device's state.
-__global__ void k_ema(const float *__restrict__ ws, int parts, int E, int first, float gamma,
-                      float *__restrict__ m, float *__restrict__ M)
+// Combine the parts and apply Eq. (1), (2) to one device's state.  A block owns 64
+// features; its 4 waves take interleaved parts and are combined through LDS.
+__global__ __launch_bounds__(256) void k_ema(const float *__restrict__ ws, int parts, int E,
+                                             int first, float gamma, float *__restrict__ m,
+                                             float *__restrict__ M)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= E) return;
-    float cmin = ws[j], cmax = ws[E + j];
-    for (int p = 1; p < parts; ++p) {
-        cmin = fminf(cmin, ws[(2 * static_cast<int64_t>(p)) * E + j]);
-        cmax = fmaxf(cmax, ws[(2 * static_cast<int64_t>(p) + 1) * E + j]);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + lane;
+    float cmin = 3.4028235e38f, cmax = -3.4028235e38f;
+    if (j < E) {
+        for (int p = wave; p < parts; p += 4) {
+            cmin = fminf(cmin, ws[(2 * static_cast<int64_t>(p)) * E + j]);
+            cmax = fmaxf(cmax, ws[(2 * static_cast<int64_t>(p) + 1) * E + j]);
+        }
+    }
+    __shared__ float red[4][2][64];
+    red[wave][0][lane] = cmin;
+    red[wave][1][lane] = cmax;
+    __syncthreads();
+    if (wave != 0 || j >= E) return;
+#pragma unroll
+    for (int w2 = 1; w2 < 4; ++w2) {
+        cmin = fminf(cmin, red[w2][0][lane]);
+        cmax = fmaxf(cmax, red[w2][1][lane]);
     }
     cmin += 0.0f;  // a zero is taken as +0
     cmax += 0.0f;
@@ -125,7 +155,7 @@ int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int f
     const int live_parts = static_cast<int>((S + rows_per_part - 1) / rows_per_part);
     const dim3 grid((E + kStripCols - 1) / kStripCols, live_parts);
     k_colminmax<<<grid, kStripLanes * kWavesPerBlock, 0, s>>>(Y, S, ldY, E, rows_per_part, ws);
-    k_ema<<<(E + 255) / 256, 256, 0, s>>>(ws, live_parts, E, first, gamma, m, M);
+    k_ema<<<(E + 63) / 64, 256, 0, s>>>(ws, live_parts, E, first, gamma, m, M);
     return hip_result(hipGetLastError());
 }
 
