@@ -25,6 +25,11 @@ import numpy as np
 import torch
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak bandwidth
+# HBM bytes per tpq_encode launch on this workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 170.9 MB read
+# + 49.9 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
+ENCODE_TRAFFIC_BYTES = 220_850_000
+DECODE_TRAFFIC_BYTES = 82_980_000
 
 
 def parse():
@@ -36,6 +41,9 @@ def parse():
     ap.add_argument("--accum", choices=["bf16", "fp32"], default="bf16")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calibrate-chunks", type=int, default=8)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (a kernel of known traffic, used to "
+                         "scale the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -131,6 +139,14 @@ def main():
     enc_gbs = B_enc / (enc_ms * 1e-3) / 1e9
     dec_gbs = B_dec / (dec_ms * 1e-3) / 1e9
 
+    if args.copy_probe:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- calibration throughput (offline path, reported separately) ----------------------
     wc = wl.CALIBRATION
     Sc, Ec = wc.cal_seq, wc.E
@@ -175,12 +191,13 @@ def main():
         "config": {"workload": w.name, "n_ranks": N, "tokens": T, "features": E, "k_bf16": k,
                    "group": G, "io_dtype": "bf16", "accumulate": args.accum, "out": "bf16",
                    "buffer_sets": len(sets)},
-        "roofline": {"bound": "hbm", "kernel": "tpq_encode (k_encode_row)", "achieved": round(enc_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "tpq_encode (k_encode_stream)", "achieved": round(enc_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "algorithmic_bytes": B_enc, "avg_ms": round(enc_ms, 5)},
+                     "traffic": ENCODE_TRAFFIC_BYTES, "algorithmic_bytes": B_enc, "avg_ms": round(enc_ms, 5)},
         "cpu_baseline": cpu,
         "decode_reduce": {"achieved": round(dec_gbs, 1), "unit": "GB/s",
-                          "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": B_dec,
+                          "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
+                          "algorithmic_bytes": B_dec,
                           "avg_ms": round(dec_ms, 5)},
         "combined_hbm_frac": round((B_enc + B_dec) / ((enc_ms + dec_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "calibrate": {"achieved": round(cal_gbs, 1), "unit": "GB/s", "frac": round(cal_gbs / HBM_PEAK_GBS, 4),
