@@ -67,6 +67,11 @@ def test_tiny_config_all_modes():
     (8192, 128, 256, 3, 2),    # 32 lanes per group
     (2048, 32, 32, 5, 5),      # 4 lanes per group
     (520, 9, 128, 1, 1),       # one row, one rank
+    (2048, 600, 64, 5, 2),     # many selected features: the encoder's whole-row LDS path
+    (4096, 497, 128, 3, 2),    # just past the streaming path's limit on k
+    (4096, 496, 128, 3, 2),    # ... and just inside it
+    (32768, 512, 128, 2, 2),   # the widest row the library takes
+    (8, 3, 32, 4, 2),          # the narrowest
 ])
 def test_shapes_random_indices(E, k, G, T, N):
     """Random selected features (the paper's "Random BF16" baseline is this case)."""
