@@ -8,15 +8,6 @@
 
 namespace tpq {
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// two floats rounded to bf16 (nearest even, one hardware instruction), packed
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-
 // round a pair of floats to bf16 and return them as floats again
 __device__ __forceinline__ void round_pair_to_bf16(float &x, float &y)
 {

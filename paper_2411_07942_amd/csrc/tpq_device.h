@@ -34,6 +34,15 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// two floats rounded to bf16 (nearest even, one hardware instruction), packed
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // Orders one wavefront's LDS traffic: writes by any lane before this point are
 // seen by reads of any lane after it.  LDS operations of a wave execute in issue
 // order, so only the compiler has to be held back.

@@ -15,7 +15,7 @@ namespace tpq {
 // chunks_padded rounds the chunk count up to whole passes.
 //
 // Layout in the caller's plan buffer (every table starts on a 16-byte boundary):
-//   PlanHeader                          64 bytes
+//   PlanHeader                          128 bytes
 //   idx      int32 [k rounded up to 4]  the selected features, ascending
 //   src_of   uint16[chunks_padded * 8]  src_of[c] = feature index of compacted
 //                                       position c; positions >= r repeat the
@@ -39,12 +39,53 @@ namespace tpq {
 //   irr_src  uint16[8 * slots]          the 8 feature indices of irregular chunk q
 //   pass_col uint16[passes + 1]         column of the first feature of pass p
 //                                       (pass_col[passes] = E)
-constexpr uint32_t kPlanMagic = 0x51505433u;  // "3TPQ"
+//
+// Tables of the encoder, which reads each chunk's features with one 16-byte load
+// straight from the row ("window" of 8 columns starting at an even column):
+//   dpos     uint32[chunks_padded]      per chunk: bits 14..0 = first 32-bit word of its
+//                                       window within the row; kDirOdd: the chunk's 8
+//                                       features start at the upper half of that word and
+//                                       end with the lower half of the next lane's first
+//                                       word; kDirSlot: the chunk takes its features from
+//                                       its slot (bits 29..16 = slot number): an outlier
+//                                       splits it, it is ragged, it must lend its window to
+//                                       outliers next to it, or the next lane's window
+//                                       does not continue its own; kDirAbsent: beyond the row
+//   dflags   uint16[chunks_padded]      scratch of the build
+//   dirr     uint16[8 * dslots]         per slot: where the chunk's 8 features sit in the
+//                                       32 bytes the chunk loads (two windows: its own and
+//                                       the 8 columns after it, pulled back where that would
+//                                       leave the row), as byte offsets 0..30; a feature out
+//                                       of reach makes the slot "wide": kDirWide | column
+//   dsel     uint32[k rounded up to 4]  per selected feature: (slot << 5) | byte offset in
+//                                       the slot that holds it, or kDirFar: in no slot
+//   pass_dirr uint16[passes + 1]        slots below pass p
+//   dpos16   uint16[segs * 64 * 8]      dpos in the form the encoder loads: the row is cut
+//                                       into segs segments of dir_P passes (dir_passes_of());
+//                                       entry [(seg * 64 + lane) * 8 + p] belongs to lane
+//                                       `lane` of the segment's pass p: bits 13..0 = first
+//                                       word of the window, kDir16Odd, kDir16Slot (slots are
+//                                       numbered in chunk order, so a lane finds its own by
+//                                       counting the flagged lanes below it)
+//   dslot8   uint32[2 * dslots]         per slot: word 0 = eight 4-bit half-word positions
+//                                       (feature e at bits 4e..4e+3) in the slot's 32 bytes,
+//                                       word 1 = byte offset of its second window in the
+//                                       row | kDirWide8 for a "wide" slot (see dirr)
+constexpr uint32_t kPlanMagic = 0x51505434u;  // "4TPQ"
 constexpr int kPlanOk = 1;
 constexpr int kPlanBadIndex = 2;
+constexpr int kPlanInternal = 3;  // a table of the build overflowed (never expected)
 constexpr uint32_t kNotRegular = 0x80000000u;
 constexpr uint32_t kNoSlot = 0x7FFFu;
 // beyond the row: flag + no slot; the low bits then hold column E - 8
+constexpr uint32_t kDirOdd = 0x8000u;
+constexpr uint32_t kDirAbsent = 0x40000000u;
+constexpr uint32_t kDirSlot = 0x80000000u;
+constexpr uint32_t kDirWide = 0x8000u;      // in a dirr entry
+constexpr uint32_t kDirFar = 0x80000000u;   // in a dsel entry
+constexpr uint32_t kDir16Odd = 0x4000u;
+constexpr uint32_t kDir16Slot = 0x8000u;
+constexpr uint32_t kDirWide8 = 0x80000000u;  // in word 1 of a dslot8 entry
 
 struct PlanHeader {
     uint32_t magic;
@@ -60,8 +101,18 @@ struct PlanHeader {
     int32_t pass_irr_offset;
     int32_t n_irr;
     int32_t irr_src_offset;
+    int32_t dpos_offset;
+    int32_t dirr_offset;
+    int32_t dsel_offset;
+    int32_t pass_dirr_offset;
+    int32_t n_dirr;       // slots in use
+    int32_t dslots;       // slots the tables have room for
+    int32_t dpos16_offset;
+    int32_t dslot8_offset;
+    int32_t dir_P;        // passes per segment the dpos16 table is laid out for
+    int32_t reserved[7];
 };
-static_assert(sizeof(PlanHeader) == 64, "plan header is 64 bytes");
+static_assert(sizeof(PlanHeader) == 128, "plan header is 128 bytes");
 
 __host__ __device__ inline int chunks_of(int r) { return (r + 7) / 8; }
 __host__ __device__ inline int chunks_padded_of(int r) { return (chunks_of(r) + 63) / 64 * 64; }
@@ -76,10 +127,34 @@ __host__ __device__ inline int irr_slots_of(int k, int r, int G)
     return (k + 1 < c ? k + 1 : c) + G / 8 - 1;
 }
 
+// ... and of the chunks that need a slot in the encoder's tables: one per selected
+// feature at most (the chunk that holds or precedes it), the ragged last chunk, the
+// last chunk of every pass, and the chunks next to the row's end
+__host__ __device__ inline int dir_slots_of(int k, int r)
+{
+    const int c = chunks_of(r);
+    const int bound = k + chunks_padded_of(r) / 64 + 4;
+    return bound < c ? bound : c;
+}
+
+// Passes per segment of the direct encoder: at most 5, segments as even as possible.
+__host__ __device__ inline int dir_passes_of(int passes)
+{
+    if (passes <= 0) return 1;
+    const int segs = (passes + 4) / 5;
+    return (passes + segs - 1) / segs;
+}
+__host__ __device__ inline int dir_segs_of(int passes)
+{
+    const int P = dir_passes_of(passes);
+    return passes > 0 ? (passes + P - 1) / P : 0;
+}
+
 __host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
 
 struct PlanOffsets {
-    int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src, total;
+    int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src;
+    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, total;
 };
 __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
 {
@@ -93,7 +168,14 @@ __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
     o.pass_irr = o.irr + 2 * cp;
     o.pass_col = o.pass_irr + pass_tab_bytes_of(r);
     o.irr_src = o.pass_col + pass_tab_bytes_of(r);
-    o.total = o.irr_src + 16 * irr_slots_of(k, r, G);
+    o.dpos = o.irr_src + 16 * irr_slots_of(k, r, G);
+    o.dflags = o.dpos + 4 * cp;
+    o.dirr = o.dflags + (2 * cp + 15) / 16 * 16;
+    o.dsel = o.dirr + 16 * dir_slots_of(k, r);
+    o.pass_dirr = o.dsel + idx_bytes_of(k);
+    o.dpos16 = o.pass_dirr + pass_tab_bytes_of(r);
+    o.dslot8 = o.dpos16 + dir_segs_of(cp / 64) * 64 * 8 * 2;
+    o.total = o.dslot8 + (8 * dir_slots_of(k, r) + 15) / 16 * 16;
     return o;
 }
 
@@ -113,6 +195,8 @@ struct EncodeArgs {
     // stage_chunks = 16-byte units of LDS each wave has for its slice of the row
     int32_t segs, seg_passes, patch_slots, stage_chunks;
     int64_t n_tasks;  // n_ranks * T * segs
+    int32_t dslots;   // slots in the plan's tables of the direct kernel
+    uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
 };
 
 struct DecodeArgs {

@@ -28,6 +28,16 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->pass_irr_offset = o.pass_irr;
         h->n_irr = 0;
         h->irr_src_offset = o.irr_src;
+        h->dpos_offset = o.dpos;
+        h->dirr_offset = o.dirr;
+        h->dsel_offset = o.dsel;
+        h->pass_dirr_offset = o.pass_dirr;
+        h->n_dirr = 0;
+        h->dslots = dir_slots_of(k, r);
+        h->dpos16_offset = o.dpos16;
+        h->dslot8_offset = o.dslot8;
+        h->dir_P = dir_passes_of(chunks_padded / 64);
+        for (int i = 0; i < 7; ++i) h->reserved[i] = 0;
     }
 }
 
@@ -138,6 +148,154 @@ __global__ void k_plan_slots(uint8_t *plan, int E, int chunks, int chunks_padded
     }
 }
 
+// ---- tables of the encoder that loads each chunk straight from the row -------------
+
+// First column of chunk c's own window: the even column at or below its first feature,
+// pulled back so that 8 columns from there stay inside the row.  Chunk 0 starts its
+// window at column 0 when selected features precede it and all fits in 16 columns, so
+// that its slot can hold them.
+__device__ inline int dir_window_a(const uint16_t *src, int c, int E, int r)
+{
+    const int nv = r - 8 * c < 8 ? r - 8 * c : 8;
+    const int c0 = src[8 * c];
+    if (c == 0 && c0 > 0 && src[nv - 1] < 16 && E >= 16) return 0;
+    const int wa = c0 & ~1;
+    return wa < E - 8 ? wa : E - 8;
+}
+
+// byte offset of column `col` in the 32 bytes (window a, then window b) of a slot, or -1
+__device__ inline int dir_slot_offset(int col, int wa, int E)
+{
+    int wb = wa + 8;
+    if (wb > E - 8) wb = E - 8;
+    if (col >= wa && col < wa + 8) return 2 * (col - wa);
+    if (col >= wb && col < wb + 8) return 16 + 2 * (col - wb);
+    return -1;
+}
+
+// dflags[c] = 1 if chunk c needs a slot.
+__global__ void k_plan_dflags(uint8_t *plan, int E, int r, int chunks, int chunks_padded,
+                              PlanOffsets o)
+{
+    const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
+    uint16_t *dflags = reinterpret_cast<uint16_t *>(plan + o.dflags);
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= chunks_padded) return;
+    uint16_t f = 0;
+    if (h->status == kPlanOk && c < chunks) {
+        const int nv = r - 8 * c < 8 ? r - 8 * c : 8;
+        const int c0 = src[8 * c], clast = src[8 * c + nv - 1];
+        const int next0 = 8 * c + 8 < r ? src[8 * c + 8] : -1;
+        const bool contiguous = nv == 8 && clast == c0 + 7;
+        // selected features inside the chunk, between it and the next one (or the row's
+        // end), or before the first chunk: this chunk's slot holds them
+        const bool hosts = clast - c0 != nv - 1 || (next0 >= 0 ? next0 : E) - clast - 1 > 0 ||
+                           (c == 0 && c0 > 0);
+        bool slot = !contiguous || hosts;
+        if (!slot && (c0 & 1)) {
+            // the 8th feature is the first half-word of the next lane's window
+            const bool next_ok = (c & 63) != 63 && next0 == c0 + 8 &&
+                                 dir_window_a(src, c + 1, E, r) == (c0 & ~1) + 8;
+            slot = !next_ok;
+        }
+        f = slot ? 1 : 0;
+    }
+    dflags[c] = f;
+}
+
+__global__ void k_plan_dslots(uint8_t *plan, int E, int r, int chunks, int chunks_padded,
+                              int dslots, PlanOffsets o)
+{
+    PlanHeader *h = reinterpret_cast<PlanHeader *>(plan);
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
+    const uint16_t *dflags = reinterpret_cast<const uint16_t *>(plan + o.dflags);
+    uint32_t *dpos = reinterpret_cast<uint32_t *>(plan + o.dpos);
+    uint16_t *dirr = reinterpret_cast<uint16_t *>(plan + o.dirr);
+    uint16_t *pass_dirr = reinterpret_cast<uint16_t *>(plan + o.pass_dirr);
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > chunks_padded) return;
+    int q = 0;
+    for (int b = 0; b < c; ++b) q += dflags[b];
+    if (c == chunks_padded) {
+        h->n_dirr = q;
+        pass_dirr[chunks_padded / 64] = static_cast<uint16_t>(q);
+        return;
+    }
+    if ((c & 63) == 0) pass_dirr[c / 64] = static_cast<uint16_t>(q);
+    // where this chunk's entry sits in the table laid out by segment
+    uint16_t *dpos16 = reinterpret_cast<uint16_t *>(plan + o.dpos16);
+    uint32_t *dslot8 = reinterpret_cast<uint32_t *>(plan + o.dslot8);
+    const int dirP = dir_passes_of(chunks_padded / 64);
+    const int pass = c / 64, seg = pass / dirP;
+    uint16_t *e16 = dpos16 + (seg * 64 + (c & 63)) * 8 + (pass - seg * dirP);
+    if (pass - seg * dirP == 0) {  // entries of passes the segment does not have
+        const int left = chunks_padded / 64 - seg * dirP;
+        for (int p = left < dirP ? left : dirP; p < 8; ++p) e16[p] = 0;
+    }
+    if (h->status != kPlanOk || c >= chunks) {
+        dpos[c] = kDirAbsent;
+        *e16 = 0;
+        return;
+    }
+    const int c0 = src[8 * c];
+    if (!dflags[c]) {
+        dpos[c] = static_cast<uint32_t>(c0 >> 1) | ((c0 & 1) ? kDirOdd : 0u);
+        *e16 = static_cast<uint16_t>((c0 >> 1) | ((c0 & 1) ? kDir16Odd : 0u));
+        return;
+    }
+    if (q >= dslots) {  // the bound of dir_slots_of() does not hold: refuse the plan
+        h->status = kPlanInternal;
+        dpos[c] = kDirAbsent;
+        *e16 = 0;
+        return;
+    }
+    const int nv = r - 8 * c < 8 ? r - 8 * c : 8;
+    const int wa = dir_window_a(src, c, E, r);
+    dpos[c] = kDirSlot | (static_cast<uint32_t>(q) << 16) | static_cast<uint32_t>(wa >> 1);
+    bool wide = false;
+    for (int e = 0; e < 8; ++e) {
+        const int col = src[8 * c + (e < nv ? e : nv - 1)];  // absent features repeat the last one
+        if (dir_slot_offset(col, wa, E) < 0) wide = true;
+    }
+    uint32_t nib = 0;
+    for (int e = 0; e < 8; ++e) {
+        const int col = src[8 * c + (e < nv ? e : nv - 1)];
+        dirr[8 * q + e] = wide ? static_cast<uint16_t>(kDirWide | col)
+                               : static_cast<uint16_t>(dir_slot_offset(col, wa, E));
+        if (!wide) nib |= static_cast<uint32_t>(dir_slot_offset(col, wa, E) >> 1) << (4 * e);
+    }
+    *e16 = static_cast<uint16_t>((wa >> 1) | kDir16Slot);
+    int wb = wa + 8;
+    if (wb > E - 8) wb = E - 8;
+    dslot8[2 * q] = nib;
+    dslot8[2 * q + 1] = static_cast<uint32_t>(2 * wb) | (wide ? kDirWide8 : 0u);
+}
+
+// One thread per selected feature: the slot that holds its column.
+__global__ void k_plan_dsel(uint8_t *plan, int E, int k, int r, PlanOffsets o)
+{
+    const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
+    const int32_t *pidx = reinterpret_cast<const int32_t *>(plan + o.idx);
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
+    const uint32_t *dpos = reinterpret_cast<const uint32_t *>(plan + o.dpos);
+    uint32_t *dsel = reinterpret_cast<uint32_t *>(plan + o.dsel);
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= (k + 3) / 4 * 4) return;
+    uint32_t v = kDirFar;
+    if (p < k && r > 0 && h->status == kPlanOk) {
+        const int j = pidx[p];
+        const int f = j - p;                       // compacted features before column j
+        const int c = f >= 1 ? (f - 1) / 8 : 0;    // the chunk that holds the one before it
+        const uint32_t d = dpos[c];
+        if (d & kDirSlot) {
+            const int off = dir_slot_offset(j, dir_window_a(src, c, E, r), E);
+            if (off >= 0) v = (((d >> 16) & 0x3FFFu) << 5) | static_cast<uint32_t>(off);
+        }
+    }
+    dsel[p] = v;
+}
+
 int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipStream_t s)
 {
     const int E = L->E, k = L->k, r = L->r;
@@ -150,6 +308,9 @@ int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipSt
     if (r > 0 && tail > 0) k_plan_pad<<<(tail + 255) / 256, 256, 0, s>>>(p, r, cp, o);
     if (cp > 0) k_plan_flags<<<(cp + 255) / 256, 256, 0, s>>>(p, r, chunks, cp, L->G / 8, o);
     k_plan_slots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, chunks, cp, irr_slots_of(k, r, L->G), o);
+    if (cp > 0) k_plan_dflags<<<(cp + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, o);
+    k_plan_dslots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, dir_slots_of(k, r), o);
+    if (k > 0) k_plan_dsel<<<((k + 3) / 4 * 4 + 255) / 256, 256, 0, s>>>(p, E, k, r, o);
     return hip_result(hipGetLastError());
 }
 
