@@ -496,18 +496,6 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     const uint32_t ln = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
-    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
-        ph->G != a.G || ph->dir_P != P)
-        return;  // the whole grid takes this branch together
-    const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
-    const u32x4 *dirr = reinterpret_cast<const u32x4 *>(a.plan + ph->dirr_offset);
-    const uint32_t *dsel = reinterpret_cast<const uint32_t *>(a.plan + ph->dsel_offset);
-    const uint16_t *pass_dirr = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_dirr_offset);
-    const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(a.plan + ph->pass_col_offset);
-    const u32x4 *dpos16 = reinterpret_cast<const u32x4 *>(a.plan + ph->dpos16_offset);
-    const uint2 *dslot8 = reinterpret_cast<const uint2 *>(a.plan + ph->dslot8_offset);
-
     const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
     const uint32_t segs = static_cast<uint32_t>(a.segs);
     const uint32_t rank = blockIdx.y;
@@ -519,18 +507,30 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     const uint32_t pass0 = seg * P, pass1 = min(pass0 + P, passes);
     const bool last_seg = pass1 == passes;
 
-    // slots and selected columns of this segment: the selected columns below the next
-    // segment's first feature that no earlier segment owns
-    const uint32_t q_lo = pass_dirr[pass0], n_q = pass_dirr[pass1] - q_lo;
-    const uint32_t s_lo = seg == 0 ? 0u : pass_col[pass0] - 512u * pass0;
-    const uint32_t n_sel = (last_seg ? static_cast<uint32_t>(a.k) : pass_col[pass1] - 512u * pass1) - s_lo;
+    // The tables sit at offsets the host knows, so the first plan reads leave together
+    // with the header's (they stay inside the plan buffer whatever it holds); nothing
+    // is done with them unless the header says that the plan is good.
+    const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + a.off_idx);
+    const u32x4 *dirr = reinterpret_cast<const u32x4 *>(a.plan + a.off_dirr);
+    const uint32_t *dsel = reinterpret_cast<const uint32_t *>(a.plan + a.off_dsel);
+    const uint2 *dslot8 = reinterpret_cast<const uint2 *>(a.plan + a.off_dslot8);
+    const uint2 *dseg = reinterpret_cast<const uint2 *>(a.plan + a.off_dseg);
+    const u32x4 *drec = reinterpret_cast<const u32x4 *>(a.plan + a.off_drec);
+    const u32x4 dp8 = drec[(seg * 64u + ln) * 2u];
+    const u32x4 rec1 = drec[(seg * 64u + ln) * 2u + 1u];
+    const uint2 sg = dseg[seg];
+    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
+    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
+        ph->G != a.G || ph->dir_P != P)
+        return;  // the whole grid takes this branch together
 
-    // per-lane plan entries (the plan is small and stays in the caches)
-    const u32x4 dp8 = dpos16[seg * 64u + ln];
-    uint2 slot8 = make_uint2(0u, 0u);
-    if (n_q > 0) slot8 = dslot8[q_lo + min(ln, n_q - 1u)];
-    uint32_t sel0 = 0;
-    if (n_sel > 0) sel0 = dsel[s_lo + min(ln, n_sel - 1u)];
+    // slots and selected columns of this segment
+    const uint32_t q_lo = sg.x & 0xFFFFu, n_q = sg.x >> 16;
+    const uint32_t s_lo = sg.y & 0xFFFFu, n_sel = sg.y >> 16;
+
+    // the segment's ln-th slot and selected feature (zero where there is none)
+    const uint2 slot8 = make_uint2(rec1.x, rec1.y);
+    const uint32_t sel0 = rec1.z;
     uint32_t d[P];
     {
         const uint32_t w4[4] = {dp8.x, dp8.y, dp8.z, dp8.w};
@@ -823,6 +823,16 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
     a.segs = (passes + P - 1) / P;
     a.segs_magic = a.segs > 1 ? static_cast<uint32_t>((1ull << 32) / a.segs + 1) : 0u;  // unused for 1
     a.dslots = dir_slots_of(a.k, a.r);
+    {
+        const PlanOffsets o = plan_offsets(a.k, a.r, a.G);
+        a.off_idx = o.idx;
+        a.off_dirr = o.dirr;
+        a.off_dsel = o.dsel;
+        a.off_dpos16 = o.dpos16;
+        a.off_dslot8 = o.dslot8;
+        a.off_dseg = o.dseg;
+        a.off_drec = o.drec;
+    }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
     const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + 4u * (64 * P / lpg));
 

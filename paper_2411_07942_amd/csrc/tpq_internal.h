@@ -67,6 +67,17 @@ namespace tpq {
 //                                       word of the window, kDir16Odd, kDir16Slot (slots are
 //                                       numbered in chunk order, so a lane finds its own by
 //                                       counting the flagged lanes below it)
+//   dseg     uint32[2 * segs]           per segment: word 0 = first slot | slots << 16, word 1 =
+//                                       first selected feature it stores | how many << 16 (the
+//                                       selected columns below the next segment's first feature
+//                                       that no earlier segment owns)
+//   drec     uint32[segs * 64 * 8]      what lane l of a wave working on segment sg loads
+//                                       first, gathered in one 32-byte record [sg * 64 + l]:
+//                                       words 0..3 = its dpos16 entries, words 4, 5 = the
+//                                       dslot8 entry of the segment's l-th slot, word 6 = the
+//                                       dsel entry of the l-th selected feature the segment
+//                                       stores (where there is none: zero, and the
+//                                       segment's first slot)
 //   dslot8   uint32[2 * dslots]         per slot: word 0 = eight 4-bit half-word positions
 //                                       (feature e at bits 4e..4e+3) in the slot's 32 bytes,
 //                                       word 1 = byte offset of its second window in the
@@ -110,7 +121,9 @@ struct PlanHeader {
     int32_t dpos16_offset;
     int32_t dslot8_offset;
     int32_t dir_P;        // passes per segment the dpos16 table is laid out for
-    int32_t reserved[7];
+    int32_t dseg_offset;
+    int32_t drec_offset;
+    int32_t reserved[5];
 };
 static_assert(sizeof(PlanHeader) == 128, "plan header is 128 bytes");
 
@@ -154,7 +167,7 @@ __host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded
 
 struct PlanOffsets {
     int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src;
-    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, total;
+    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, total;
 };
 __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
 {
@@ -175,7 +188,9 @@ __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
     o.pass_dirr = o.dsel + idx_bytes_of(k);
     o.dpos16 = o.pass_dirr + pass_tab_bytes_of(r);
     o.dslot8 = o.dpos16 + dir_segs_of(cp / 64) * 64 * 8 * 2;
-    o.total = o.dslot8 + (8 * dir_slots_of(k, r) + 15) / 16 * 16;
+    o.dseg = o.dslot8 + (8 * dir_slots_of(k, r) + 15) / 16 * 16;
+    o.drec = o.dseg + (8 * dir_segs_of(cp / 64) + 15) / 16 * 16;
+    o.total = o.drec + dir_segs_of(cp / 64) * 64 * 32;
     return o;
 }
 
@@ -197,6 +212,8 @@ struct EncodeArgs {
     int64_t n_tasks;  // n_ranks * T * segs
     int32_t dslots;   // slots in the plan's tables of the direct kernel
     uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
+    // byte offsets of the plan's tables (what the header holds, known to the host too)
+    int32_t off_idx, off_dirr, off_dsel, off_dpos16, off_dslot8, off_dseg, off_drec;
 };
 
 struct DecodeArgs {

@@ -37,7 +37,9 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->dpos16_offset = o.dpos16;
         h->dslot8_offset = o.dslot8;
         h->dir_P = dir_passes_of(chunks_padded / 64);
-        for (int i = 0; i < 7; ++i) h->reserved[i] = 0;
+        h->dseg_offset = o.dseg;
+        h->drec_offset = o.drec;
+        for (int i = 0; i < 5; ++i) h->reserved[i] = 0;
     }
 }
 
@@ -296,6 +298,45 @@ __global__ void k_plan_dsel(uint8_t *plan, int E, int k, int r, PlanOffsets o)
     dsel[p] = v;
 }
 
+// One thread per segment of the direct encoder: its slots and selected features.
+__global__ void k_plan_dseg(uint8_t *plan, int k, int chunks_padded, PlanOffsets o)
+{
+    const uint16_t *pass_dirr = reinterpret_cast<const uint16_t *>(plan + o.pass_dirr);
+    const uint16_t *pass_col = reinterpret_cast<const uint16_t *>(plan + o.pass_col);
+    uint32_t *dseg = reinterpret_cast<uint32_t *>(plan + o.dseg);
+    const int passes = chunks_padded / 64, P = dir_passes_of(passes);
+    const int sg = blockIdx.x * blockDim.x + threadIdx.x;
+    if (sg >= dir_segs_of(passes)) return;
+    const int p0 = sg * P, p1 = p0 + P < passes ? p0 + P : passes;
+    const uint32_t q_lo = pass_dirr[p0], q_hi = pass_dirr[p1];
+    const uint32_t s_lo = sg == 0 ? 0u : pass_col[p0] - 512u * p0;
+    const uint32_t s_hi = p1 == passes ? static_cast<uint32_t>(k) : pass_col[p1] - 512u * p1;
+    dseg[2 * sg] = q_lo | ((q_hi - q_lo) << 16);
+    dseg[2 * sg + 1] = s_lo | ((s_hi - s_lo) << 16);
+}
+
+// One thread per (segment, lane): the record a lane of the direct encoder starts from.
+__global__ void k_plan_drec(uint8_t *plan, int chunks_padded, PlanOffsets o)
+{
+    const uint32_t *dpos16 = reinterpret_cast<const uint32_t *>(plan + o.dpos16);
+    const uint32_t *dslot8 = reinterpret_cast<const uint32_t *>(plan + o.dslot8);
+    const uint32_t *dsel = reinterpret_cast<const uint32_t *>(plan + o.dsel);
+    const uint32_t *dseg = reinterpret_cast<const uint32_t *>(plan + o.dseg);
+    uint32_t *drec = reinterpret_cast<uint32_t *>(plan + o.drec);
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= dir_segs_of(chunks_padded / 64) * 64) return;
+    const int sg = i / 64;
+    const uint32_t l = i % 64;
+    const uint32_t q_lo = dseg[2 * sg] & 0xFFFFu, n_q = dseg[2 * sg] >> 16;
+    const uint32_t s_lo = dseg[2 * sg + 1] & 0xFFFFu, n_sel = dseg[2 * sg + 1] >> 16;
+    uint32_t *rec = drec + 8 * i;
+    for (int w = 0; w < 4; ++w) rec[w] = dpos16[4 * i + w];
+    rec[4] = l < n_q ? dslot8[2 * (q_lo + l)] : 0u;
+    rec[5] = l < n_q ? dslot8[2 * (q_lo + l) + 1] : 0u;
+    rec[6] = l < n_sel ? dsel[s_lo + l] : (q_lo << 5);  // idle lanes read the segment's first slot
+    rec[7] = 0u;
+}
+
 int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipStream_t s)
 {
     const int E = L->E, k = L->k, r = L->r;
@@ -310,7 +351,9 @@ int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipSt
     k_plan_slots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, chunks, cp, irr_slots_of(k, r, L->G), o);
     if (cp > 0) k_plan_dflags<<<(cp + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, o);
     k_plan_dslots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, dir_slots_of(k, r), o);
+    if (cp > 0) k_plan_dseg<<<1, 64, 0, s>>>(p, k, cp, o);
     if (k > 0) k_plan_dsel<<<((k + 3) / 4 * 4 + 255) / 256, 256, 0, s>>>(p, E, k, r, o);
+    if (cp > 0) k_plan_drec<<<(dir_segs_of(cp / 64) * 64 + 255) / 256, 256, 0, s>>>(p, cp, o);
     return hip_result(hipGetLastError());
 }
 
