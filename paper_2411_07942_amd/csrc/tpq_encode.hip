@@ -693,13 +693,23 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
             static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
             static_cast<int64_t>(t) * a.pitch_meta);
         const uint32_t g0 = pass0 * (64 / LPG);
-#pragma unroll
-        for (uint32_t gl0 = 0; gl0 < static_cast<uint32_t>(GPS); gl0 += 64) {
-            const uint32_t gl = gl0 + ln;
+        if (GPS <= 32) {
+            // one store instruction for both: lanes 0..31 scales, lanes 32..63 zeros
+            const uint32_t gl = ln & 31u;
+            const bool is_zero = ln >= 32u;
             if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
                 const uint32_t m = l_meta[gl];
-                scale[g0 + gl] = static_cast<uint16_t>(m & 0xFFFFu);
-                zero[g0 + gl] = static_cast<uint16_t>(m >> 16);
+                (is_zero ? zero : scale)[g0 + gl] = static_cast<uint16_t>(is_zero ? m >> 16 : m & 0xFFFFu);
+            }
+        } else {
+#pragma unroll
+            for (uint32_t gl0 = 0; gl0 < static_cast<uint32_t>(GPS); gl0 += 64) {
+                const uint32_t gl = gl0 + ln;
+                if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
+                    const uint32_t m = l_meta[gl];
+                    scale[g0 + gl] = static_cast<uint16_t>(m & 0xFFFFu);
+                    zero[g0 + gl] = static_cast<uint16_t>(m >> 16);
+                }
             }
         }
     }
