@@ -26,10 +26,10 @@ import torch
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak bandwidth
 # HBM bytes per tpq_encode launch on this workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 170.9 MB read
-# + 49.9 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
-ENCODE_TRAFFIC_BYTES = 220_850_000
-DECODE_TRAFFIC_BYTES = 82_980_000
+# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 179.4 MB read
+# + 50.0 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
+ENCODE_TRAFFIC_BYTES = 229_460_000
+DECODE_TRAFFIC_BYTES = 83_890_000
 
 
 def parse():
@@ -38,7 +38,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=6, help="independent buffer sets rotated per step")
-    ap.add_argument("--accum", choices=["bf16", "fp32"], default="bf16")
+    ap.add_argument("--accum", choices=["bf16", "fp32"], default="fp32",
+                    help="arithmetic of the sum over ranks in tpq_decode_reduce")
+    ap.add_argument("--event-stride", type=int, default=8,
+                    help="kernel durations are sampled with HIP events on every n-th timed step "
+                         "(an event record costs about as much idle time as it measures)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calibrate-chunks", type=int, default=8)
     ap.add_argument("--copy-probe", action="store_true",
@@ -115,21 +119,42 @@ def main():
     # ---- timed region ---------------------------------------------------------------------
     for i in range(args.warmup):
         step(sets[i % len(sets)])
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    stride = max(1, args.event_stride)
+    sampled = list(range(0, args.steps, stride))
+    ev = {i: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         bufs = sets[i % len(sets)]
-        ev[i][0].record()
-        bufs[3]()
-        ev[i][1].record()
-        bufs[4]()
-        ev[i][2].record()
+        e = ev.get(i)
+        if e is None:
+            bufs[3]()
+            bufs[4]()
+        else:
+            e[0].record()
+            bufs[3]()
+            e[1].record()
+            bufs[4]()
+            e[2].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / args.steps
-    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev.values()]))
+    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev.values()]))
+
+    # the other accumulate mode of tpq_decode_reduce, for the record (not part of `value`)
+    other = tpq.ACC_BF16 if accum == tpq.ACC_FP32 else tpq.ACC_FP32
+    other_calls = [tpq.decode_reduce_call(L, plan, b[1], b[2], other) for b in sets]
+    for c in other_calls:
+        c()
+    oe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(24)]
+    torch.cuda.synchronize()
+    for i, e in enumerate(oe):
+        e[0].record()
+        other_calls[i % len(other_calls)]()
+        e[1].record()
+    torch.cuda.synchronize()
+    other_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in oe]))
 
     W = L.wire_bytes_per_row
     B_in = N * T * E * 2
@@ -191,14 +216,17 @@ def main():
         "config": {"workload": w.name, "n_ranks": N, "tokens": T, "features": E, "k_bf16": k,
                    "group": G, "io_dtype": "bf16", "accumulate": args.accum, "out": "bf16",
                    "buffer_sets": len(sets)},
-        "roofline": {"bound": "hbm", "kernel": "tpq_encode (k_encode_stream)", "achieved": round(enc_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "tpq_encode (k_encode_direct)", "achieved": round(enc_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
                      "traffic": ENCODE_TRAFFIC_BYTES, "algorithmic_bytes": B_enc, "avg_ms": round(enc_ms, 5)},
         "cpu_baseline": cpu,
         "decode_reduce": {"achieved": round(dec_gbs, 1), "unit": "GB/s",
                           "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
                           "algorithmic_bytes": B_dec,
-                          "avg_ms": round(dec_ms, 5)},
+                          "avg_ms": round(dec_ms, 5), "accumulate": args.accum,
+                          "other_mode": {"accumulate": "bf16" if other == tpq.ACC_BF16 else "fp32",
+                                         "avg_ms": round(other_ms, 5)}},
+        "event_stride": stride,
         "combined_hbm_frac": round((B_enc + B_dec) / ((enc_ms + dec_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "calibrate": {"achieved": round(cal_gbs, 1), "unit": "GB/s", "frac": round(cal_gbs / HBM_PEAK_GBS, 4),
                       "chunk": [Sc, Ec], "avg_ms": round(cal_ms, 5)},
