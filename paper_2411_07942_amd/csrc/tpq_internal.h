@@ -206,10 +206,10 @@ struct EncodeArgs {
     int32_t n_ranks;
     int64_t T, ldY;
     int64_t pitch_codes, pitch_meta, pitch_outl;
-    // streaming kernels: a row is cut into `segs` segments of `seg_passes` passes;
-    // stage_chunks = 16-byte units of LDS each wave has for its slice of the row
-    int32_t segs, seg_passes, patch_slots, stage_chunks;
-    int64_t n_tasks;  // n_ranks * T * segs
+    // direct kernel: a row is cut into `segs` segments of `seg_passes` passes;
+    // patch_slots = 32-byte LDS slots each wave has for split chunks
+    int32_t segs, seg_passes, patch_slots;
+    int64_t n_tasks;  // T * segs (per rank)
     int32_t dslots;   // slots in the plan's tables of the direct kernel
     uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
     // byte offsets of the plan's tables (what the header holds, known to the host too)

@@ -106,6 +106,34 @@ def test_adjacent_and_edge_outliers():
     _codec_case(w, Ys, idx)
 
 
+@pytest.mark.parametrize("name,cols", [
+    ("one_odd_shift", [3]),                                   # every later chunk starts on an odd column
+    ("run_in_the_middle", list(range(100, 121))),             # a chunk whose features lie 21 columns apart
+    ("run_at_the_end", list(range(2048 - 12, 2048))),
+    ("run_at_the_start", list(range(0, 12))),
+    ("every_other", list(range(200, 264, 2))),                # four selected columns inside each chunk
+    ("every_third", list(range(601, 700, 3))),
+    ("across_pass_boundaries", list(range(505, 521)) + [1033, 1034, 1040, 1551]),
+    ("last_column_only", [2047]),
+    ("first_column_only", [0]),
+    ("pairs", [c for b in range(64, 1900, 97) for c in (b, b + 1)]),
+])
+def test_outlier_patterns(name, cols):
+    """Index sets that exercise every way a chunk can be cut (slots, second windows,
+    features and selected columns out of a slot's reach)."""
+    E, G, T, N = 2048, 128, 3, 2
+    idx = np.array(sorted(set(cols)), np.int32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(len(cols) * 7 + cols[0])
+    Ys = []
+    for i in range(N):
+        x = torch.randn((T, E), generator=g, device="cuda")
+        x[:, torch.as_tensor(idx.astype(np.int64), device="cuda")] *= 60.0
+        Ys.append(x.to(torch.bfloat16))
+    w = dataclasses.replace(wl.TINY, N=N, T=T, E=E, k=idx.size, G=G)
+    _codec_case(w, Ys, idx)
+
+
 def test_denormal_and_huge_values():
     E, G, T = 512, 128, 4
     x = torch.zeros((T, E), device="cuda")
