@@ -51,5 +51,23 @@ def build(extra_flags=(), jobs: int = 5) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(ROOT, "tests", "probes", "hw_probe.hip")
+PROBE_BIN = os.path.join(ROOT, "tests", "probes", "hw_probe")
+
+
+def build_probe() -> str:
+    """The stand-alone program that checks the instruction behaviour the kernels rely on
+    (run by the GPU tests)."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O2", "-ffp-contract=off",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", PROBE_SRC, "-o", PROBE_BIN + ".tmp%d" % os.getpid()]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for hw_probe.hip:\n" + r.stderr)
+    os.replace(PROBE_BIN + ".tmp%d" % os.getpid(), PROBE_BIN)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:]))
+    print(build_probe())

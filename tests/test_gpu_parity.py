@@ -199,6 +199,19 @@ def test_determinism():
         assert blob == first
 
 
+def test_hardware_behaviour_probe():
+    """The instruction behaviour the kernels rely on for bit-exact results (rounding of the
+    byte and bf16 conversions, the two division shortcuts checked against IEEE division --
+    the reciprocal for every bf16 scale --, lane order of the DPP shift, byte order of the
+    permute), checked by a stand-alone program that build() compiles."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "probes", "hw_probe")
+    assert os.path.exists(exe), "tests/probes/hw_probe is not built: run __graft_entry__.build()"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0 and "HW PROBE OK" in r.stdout, r.stdout + r.stderr
+
+
 def _sample_rows(T, n, seed):
     rng = np.random.default_rng(seed)
     rows = set(rng.choice(T, min(n, T), replace=False).tolist()) | {0, T - 1, T // 2}

@@ -292,3 +292,17 @@ def test_bad_arguments_are_rejected():
     for bad in ([3, 3], [5, 2], [16], [-1]):
         with pytest.raises(ValueError):
             oracle.encode(Y, np.array(bad, np.int32), 8)
+
+
+def test_division_by_15_shortcut_is_exact(tmp_path):
+    """(max - min) / 15, the quantiser's scale (Sec. 2): the GPU kernels multiply by fl(1/15)
+    and correct once with a fused multiply-add; the oracle divides.  Equal for every mantissa
+    (checked here at exponents across the range, including the smallest normal ones)."""
+    import os
+    import subprocess
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "div15_check.c")
+    exe = str(tmp_path / "div15_check")
+    subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-o", exe, src, "-lm"], check=True)
+    r = subprocess.run([exe, "1", "2", "5", "27", "100", "127", "128", "200", "253", "254"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip() == "0", r.stdout + r.stderr
