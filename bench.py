@@ -38,8 +38,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=6, help="independent buffer sets rotated per step")
-    ap.add_argument("--accum", choices=["bf16", "fp32"], default="fp32",
-                    help="arithmetic of the sum over ranks in tpq_decode_reduce")
+    ap.add_argument("--accum", choices=["bf16", "fp32"], default="bf16",
+                    help="arithmetic of the sum over ranks in tpq_decode_reduce (the other mode is "
+                         "timed beside it and reported under decode_reduce.other_mode)")
     ap.add_argument("--event-stride", type=int, default=8,
                     help="kernel durations are sampled with HIP events on every n-th timed step "
                          "(an event record costs about as much idle time as it measures)")

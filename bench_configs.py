@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Timings of the codec on the other benchmark configurations (one MI355X).
+
+bench.py measures the headline number (the Llama-2-13B-shaped prefill block, whole path).
+This script adds what a deployment asks next, one JSON line per section:
+
+  llama   the same block: encode of all 8 simulated ranks, encode of ONE rank (a device's real
+          share), decode_reduce in both accumulate modes, and the per-device-share bandwidth
+          (B_enc / N + B_dec) / (t_enc1 + t_dec);
+  gemma   the Gemma-2-27B-shaped decode regime: 92 blocks of [64 x 4608], each with its own outlier
+          set; per block one tpq_encode of the device's own partial sum and one tpq_decode_reduce
+          over 8 messages, (a) launched back to back, (b) the same 184 launches replayed from one
+          HIP graph (every replay is checked against the eager result);
+  large   the large prefill stress block (16 ranks, [16384 x 8192]) in its four variants, fp32
+          accumulate, bf16 and fp32 output.
+
+Inputs are seeded synthetic activations (workloads/), resident in HBM before timing.  The selected
+features of each block are its planted outlier columns filled up to k with random other columns (a
+stand-in for a calibration run, which bench.py and the tests exercise).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+HBM_PEAK_GBS = 8000.0
+
+
+def idx_for(wl, w, block=0):
+    """The block's planted outlier columns, filled up to k with seeded random other columns
+    (what a calibration run returns when the remaining ranges are nearly equal)."""
+    cols, _ = wl.outlier_columns(w, block)
+    cols = cols.numpy()[: w.k]
+    others = np.setdiff1d(np.arange(w.E), cols)
+    rng = np.random.default_rng(wl.seed_for(w, block, 0, 7))
+    rest = rng.choice(others, w.k - cols.size, replace=False)
+    return np.sort(np.concatenate([cols, rest])).astype(np.int32)
+
+
+def timed(calls, reps, sync_every=None):
+    """Average microseconds per sweep over `calls`, launched back to back."""
+    for c in calls:
+        c()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for c in calls:
+            c()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e6 / reps
+
+
+def section_llama(tpq, wl, args):
+    w = wl.LLAMA_PREFILL
+    N, T, E = w.N, w.T, w.E
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
+    tpq.plan_check(L, plan)
+    sets = []
+    for s in range(6):
+        Ys = wl.partial_sums(w, block=s, device=dev)
+        msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+        out = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        sets.append(dict(enc=tpq.encode_call(L, plan, Ys, msgs),
+                         enc1=tpq.encode_call(L, plan, Ys[:1], msgs[:1]),
+                         dec_bf16=tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_BF16),
+                         dec_fp32=tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_FP32), keep=(Ys, msgs, out)))
+    W = L.wire_bytes_per_row
+    B_enc, B_dec = N * T * (2 * E + W), T * (N * W + 2 * E)
+    t = {k: timed([s[k] for s in sets], 40) / len(sets) for k in ("enc", "enc1", "dec_bf16", "dec_fp32")}
+    share = (B_enc / N + B_dec) / ((t["enc1"] + t["dec_bf16"]) * 1e-6) / 1e9
+    return {"section": "llama2_13b_prefill", "us": {k: round(v, 2) for k, v in t.items()},
+            "encode_all_ranks_GBps": round(B_enc / t["enc"] / 1e3, 1),
+            "encode_one_rank_GBps": round(B_enc / N / t["enc1"] / 1e3, 1),
+            "decode_reduce_GBps": {"bf16": round(B_dec / t["dec_bf16"] / 1e3, 1), "fp32": round(B_dec / t["dec_fp32"] / 1e3, 1)},
+            "per_device_share_GBps": round(share, 1), "per_device_share_frac_of_peak": round(share / HBM_PEAK_GBS, 4),
+            "note": "launches back to back (no events between them), 6 rotating buffer sets"}
+
+
+def section_gemma(tpq, wl, args):
+    w = wl.GEMMA_DECODE
+    N, T, E, nb = w.N, w.T, w.E, w.blocks
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    blocks = []
+    for b in range(nb):
+        plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w, b)).to(dev))
+        Ys = wl.partial_sums(w, block=b, device=dev)
+        msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+        tpq.encode(L, plan, Ys, msgs)          # the other ranks' messages, as the all-gather would deliver them
+        out = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        blocks.append(dict(enc1=tpq.encode_call(L, plan, Ys[:1], msgs[:1]),
+                           dec=tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_BF16), out=out, keep=(plan, Ys, msgs)))
+    tpq.plan_check(L, blocks[-1]["keep"][0])
+    calls = [c for blk in blocks for c in (blk["enc1"], blk["dec"])]
+    eager_us = timed(calls, 20)
+    eager = [blk["out"].clone() for blk in blocks]
+
+    # the same launches from one graph
+    graph_us, graph_ok = None, None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for c in calls:
+                c()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for c in calls:
+                c()
+        graph_ok = True
+        for rep in range(3):          # replays with eager work and synchronisation in between
+            for blk in blocks:
+                blk["out"].zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            graph_ok = graph_ok and all(torch.equal(blk["out"], e) for blk, e in zip(blocks, eager))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) * 1e6 / 20
+    except Exception as exc:  # graph capture is optional: report why it was not measured
+        graph_ok = "not measured: %s" % (str(exc).splitlines()[0] if str(exc) else type(exc).__name__)
+    W = L.wire_bytes_per_row
+    B_blk = T * (2 * E + W) + T * (N * W + 2 * E)
+    res = {"section": "gemma2_27b_decode", "blocks": nb,
+           "eager_us_per_block": round(eager_us / nb, 2), "eager_GBps": round(B_blk * nb / eager_us / 1e3, 1),
+           "graph_us_per_block": None if graph_us is None else round(graph_us / nb, 2),
+           "graph_matches_eager": graph_ok,
+           "note": "per block: tpq_encode of one rank + tpq_decode_reduce over 8 messages; launch-latency-bound regime"}
+    return res
+
+
+def section_large(tpq, wl, args):
+    dev = "cuda"
+    results = []
+    for w in wl.large_variants():
+        N, T, E = w.N, w.T, w.E
+        L = tpq.layout_init(E, w.k, w.G)
+        plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
+        tpq.plan_check(L, plan)
+        Ys = wl.partial_sums(w, device=dev)
+        msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+        out16 = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        out32 = torch.empty((T, E), dtype=torch.float32, device=dev)
+        enc = tpq.encode_call(L, plan, Ys, msgs)
+        d16 = tpq.decode_reduce_call(L, plan, msgs, out16, tpq.ACC_FP32)
+        d32 = tpq.decode_reduce_call(L, plan, msgs, out32, tpq.ACC_FP32)
+        W = L.wire_bytes_per_row
+        B_enc, B_d16, B_d32 = N * T * (2 * E + W), T * (N * W + 2 * E), T * (N * W + 4 * E)
+        t_enc, t_d16, t_d32 = timed([enc], 5), timed([d16], 5), timed([d32], 5)
+        results.append({"variant": w.name, "encode_us": round(t_enc, 1), "encode_GBps": round(B_enc / t_enc / 1e3, 1),
+                        "decode_bf16_out_us": round(t_d16, 1), "decode_bf16_out_GBps": round(B_d16 / t_d16 / 1e3, 1),
+                        "decode_fp32_out_us": round(t_d32, 1), "decode_fp32_out_GBps": round(B_d32 / t_d32 / 1e3, 1),
+                        "partials_GBps": round(N * T * E * 2 / (t_enc + t_d16) / 1e3, 1)})
+        del Ys, msgs, out16, out32, enc, d16, d32
+        torch.cuda.empty_cache()
+    return {"section": "large_prefill", "variants": results,
+            "note": "16 ranks x [16384 x 8192], fp32 accumulate; one buffer set (5.6 GB, far beyond the caches)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--sections", default="llama,gemma,large")
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        sys.exit("bench_configs.py: no GPU visible")
+    import paper_2411_07942_amd as tpq
+    import workloads as wl
+    table = {"llama": section_llama, "gemma": section_gemma, "large": section_large}
+    for name in args.sections.split(","):
+        print(json.dumps(table[name](tpq, wl, args)), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -127,9 +127,13 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     const uint32_t q_lo = sg.x & 0xFFFFu, n_q = sg.x >> 16;
     const uint32_t s_lo = sg.y & 0xFFFFu, n_sel = sg.y >> 16;
 
-    // the segment's ln-th slot and selected feature (zero where there is none)
+    // the segment's ln-th and (64 + ln)-th slot and selected feature (zero where there is
+    // none); the second record is fetched only where a segment has that many
     const uint2 slot8 = make_uint2(rec1.x, rec1.y);
     const uint32_t sel0 = rec1.z;
+    u32x4 rec2 = {0u, 0u, 0u, 0u};
+    if (n_q > 64 || n_sel > 64)
+        rec2 = reinterpret_cast<const u32x4 *>(a.plan + a.off_drec2)[seg * 64u + ln];
     uint32_t d[P];
     {
         const uint32_t w4[4] = {dp8.x, dp8.y, dp8.z, dp8.w};
@@ -144,8 +148,9 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     for (int p = 0; p < P; ++p)
         raw[p] = __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_a4 *>(yrow + 4u * (d[p] & 0x3FFFu)));
-    u32x4 win_b = {0u, 0u, 0u, 0u};
+    u32x4 win_b = {0u, 0u, 0u, 0u}, win_b2 = {0u, 0u, 0u, 0u};
     if (ln < n_q) win_b = *reinterpret_cast<const u32x4_a4 *>(yrow + (slot8.y & 0x1FFFFu));
+    if (64u + ln < n_q) win_b2 = *reinterpret_cast<const u32x4_a4 *>(yrow + (rec2.y & 0x1FFFFu));
 
     constexpr int GPS = 64 * P / LPG;  // groups per segment
     extern __shared__ u32x4 smem_direct[];
@@ -175,7 +180,8 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
         }
     }
     if (ln < n_q) *reinterpret_cast<u32x4 *>(slots + 32u * ln + 16u) = win_b;
-    for (uint32_t q0 = 64; q0 < n_q; q0 += 64) {  // more than 64 slots in a segment: rare
+    if (64u + ln < n_q) *reinterpret_cast<u32x4 *>(slots + 32u * (64u + ln) + 16u) = win_b2;
+    for (uint32_t q0 = 128; q0 < n_q; q0 += 64) {  // more than 128 slots in a segment: rare
         const uint32_t q = q0 + ln;
         if (q < n_q)
             *reinterpret_cast<u32x4 *>(slots + 32u * q + 16u) =
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
                              static_cast<int64_t>(t) * a.pitch_outl) + s_lo;
         for (uint32_t p0 = 0; p0 < n_sel; p0 += 64) {
             const uint32_t p = p0 + ln, pc = min(p, n_sel - 1u);
-            const uint32_t e = p0 == 0 ? sel0 : dsel[s_lo + pc];
+            const uint32_t e = p0 == 0 ? sel0 : (p0 == 64 ? rec2.z : dsel[s_lo + pc]);
             const bool far = (e & kDirFar) != 0;
             uint32_t val = TPQ_LDS_HW(slots + (far ? 0u : e - 32u * q_lo));
             if (far) val = TPQ_HW(yrow + 2u * static_cast<uint32_t>(idx[s_lo + pc]));
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     }
     for (uint32_t q0 = 0; q0 < n_q; q0 += 64) {
         const uint32_t q = q0 + ln, qc = min(q, n_q - 1u);
-        const uint2 ent = q0 == 0 ? slot8 : dslot8[q_lo + qc];
+        const uint2 ent = q0 == 0 ? slot8 : (q0 == 64 ? make_uint2(rec2.x, rec2.y) : dslot8[q_lo + qc]);
         const uint8_t *sl = slots + 32u * qc;
         const uint32_t nib = ent.x;
         u32x4 g;
@@ -391,6 +397,7 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         a.off_dslot8 = o.dslot8;
         a.off_dseg = o.dseg;
         a.off_drec = o.drec;
+        a.off_drec2 = o.drec2;
     }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
     const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + 4u * (64 * P / lpg));

@@ -78,6 +78,8 @@ namespace tpq {
 //                                       dsel entry of the l-th selected feature the segment
 //                                       stores (where there is none: zero, and the
 //                                       segment's first slot)
+//   drec2    uint32[segs * 64 * 4]      the same for the segment's (64 + l)-th slot and selected
+//                                       feature: words 0, 1 = dslot8 entry, word 2 = dsel entry
 //   dslot8   uint32[2 * dslots]         per slot: word 0 = eight 4-bit half-word positions
 //                                       (feature e at bits 4e..4e+3) in the slot's 32 bytes,
 //                                       word 1 = byte offset of its second window in the
@@ -123,7 +125,8 @@ struct PlanHeader {
     int32_t dir_P;        // passes per segment the dpos16 table is laid out for
     int32_t dseg_offset;
     int32_t drec_offset;
-    int32_t reserved[5];
+    int32_t drec2_offset;
+    int32_t reserved[4];
 };
 static_assert(sizeof(PlanHeader) == 128, "plan header is 128 bytes");
 
@@ -167,7 +170,7 @@ __host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded
 
 struct PlanOffsets {
     int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src;
-    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, total;
+    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, drec2, total;
 };
 __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
 {
@@ -190,7 +193,8 @@ __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
     o.dslot8 = o.dpos16 + dir_segs_of(cp / 64) * 64 * 8 * 2;
     o.dseg = o.dslot8 + (8 * dir_slots_of(k, r) + 15) / 16 * 16;
     o.drec = o.dseg + (8 * dir_segs_of(cp / 64) + 15) / 16 * 16;
-    o.total = o.drec + dir_segs_of(cp / 64) * 64 * 32;
+    o.drec2 = o.drec + dir_segs_of(cp / 64) * 64 * 32;
+    o.total = o.drec2 + dir_segs_of(cp / 64) * 64 * 16;
     return o;
 }
 
@@ -213,7 +217,7 @@ struct EncodeArgs {
     int32_t dslots;   // slots in the plan's tables of the direct kernel
     uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
     // byte offsets of the plan's tables (what the header holds, known to the host too)
-    int32_t off_idx, off_dirr, off_dsel, off_dpos16, off_dslot8, off_dseg, off_drec;
+    int32_t off_idx, off_dirr, off_dsel, off_dpos16, off_dslot8, off_dseg, off_drec, off_drec2;
 };
 
 struct DecodeArgs {

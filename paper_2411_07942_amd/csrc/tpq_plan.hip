@@ -39,7 +39,8 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->dir_P = dir_passes_of(chunks_padded / 64);
         h->dseg_offset = o.dseg;
         h->drec_offset = o.drec;
-        for (int i = 0; i < 5; ++i) h->reserved[i] = 0;
+        h->drec2_offset = o.drec2;
+        for (int i = 0; i < 4; ++i) h->reserved[i] = 0;
     }
 }
 
@@ -335,6 +336,12 @@ __global__ void k_plan_drec(uint8_t *plan, int chunks_padded, PlanOffsets o)
     rec[5] = l < n_q ? dslot8[2 * (q_lo + l) + 1] : 0u;
     rec[6] = l < n_sel ? dsel[s_lo + l] : (q_lo << 5);  // idle lanes read the segment's first slot
     rec[7] = 0u;
+    uint32_t *rec2 = reinterpret_cast<uint32_t *>(plan + o.drec2) + 4 * i;
+    const uint32_t l2 = l + 64u;
+    rec2[0] = l2 < n_q ? dslot8[2 * (q_lo + l2)] : 0u;
+    rec2[1] = l2 < n_q ? dslot8[2 * (q_lo + l2) + 1] : 0u;
+    rec2[2] = l2 < n_sel ? dsel[s_lo + l2] : (q_lo << 5);
+    rec2[3] = 0u;
 }
 
 int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipStream_t s)
