@@ -35,11 +35,24 @@
  *     at the end, or left fp32) or literally in bf16 (every term and every
  *     partial sum rounded to bf16).
  *
+ *   static symmetric mode (paper Sec. 3 "Calibration" and "Selecting High
+ *   Precision Features": every feature on every device has static,
+ *   independent quantisation parameters from calibration, the range is
+ *   R = 2*max(-m, M), and all features that are not kept in BF16 are
+ *   symmetrically quantised to Int4).  The paper gives neither the step nor
+ *   the code set; the reading taken here is the common symmetric one with
+ *   the full signed range: step = R/15, code = rint(x * (1/step)) clamped to
+ *   -8..7, x^ = code * step, travelling as the nibble code + 8.  A feature
+ *   whose calibrated range vanishes (step < 1e-30) is sent as code 0 and
+ *   comes back as 0.  Nothing but codes and the BF16 features travels.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (brute force over all 16 codes in float64, verbatim outliers, half-step
  * error bound, closed-form bit counts, Irwin-Hall variance of the summed
  * error, hand-worked EMA examples, numpy stable-sort top-k, plain-sum special
- * case k = E).  Parity unpinned: the byte layout of the message (nibble
+ * case k = E; for the static mode: half-step error inside the calibrated
+ * range, saturation outside, all 16 codes by brute force in float64, the
+ * worked example under tests/golden).  Parity unpinned: the byte layout of the message (nibble
  * order, pad nibble, section order) is not fixed by the paper; it is this
  * build's own choice and is only checked against its written description.
  *
@@ -364,6 +377,128 @@ int orc_decode_reduce(int N, int64_t T, int E, int k, int G,
                     float z = bf16_to_f32(zero[i][t * ng + c / G]);
                     float prod = (float)code * s; /* exact: 4 bits x 8 bits */
                     x = prod + z;
+                }
+                if (accum == ORC_ACC_BF16) {
+                    x = round_to_bf16(x);
+                    acc = (i == 0) ? x : round_to_bf16(acc + x);
+                } else {
+                    acc = (i == 0) ? x : acc + x;
+                }
+            }
+            if (of)
+                of[j] = acc;
+            else
+                ob[j] = f32_to_bf16(acc);
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/* ---- static symmetric mode --------------------------------------------- */
+
+/*
+ * Per device i and feature j (paper Sec. 3): R = 2*max(-m, M), step = R/15,
+ * inv = 1/step; a vanishing range gives step = inv = 0.
+ * m, M, step, inv: float [N][E].
+ */
+int orc_static_params(const float *m, const float *M, int N, int E, float *step, float *inv)
+{
+    if (!m || !M || !step || !inv || N < 1 || E < 1) return ORC_ERR_ARG;
+    for (int64_t q = 0; q < (int64_t)N * E; ++q) {
+        float lo = -m[q], hi = M[q];
+        float R = 2.0f * (lo > hi ? lo : hi);
+        R += 0.0f;
+        float d = R / 15.0f;
+        if (!(d >= 1e-30f)) {
+            step[q] = 0.0f;
+            inv[q] = 0.0f;
+        } else {
+            step[q] = d;
+            inv[q] = 1.0f / d;
+        }
+    }
+    return ORC_OK;
+}
+
+/*
+ * One device's partial sums -> outl bf16 [T][k] and codes u8 [T][ceil(r/2)]
+ * (two nibbles per byte, low nibble first, nibble = code + 8).
+ * inv: this device's float [E], in feature order.
+ */
+int orc_encode_static(const uint16_t *Y, int64_t T, int64_t ldY, int E, int k,
+                      const int32_t *idx_sorted, const float *inv, uint16_t *outl,
+                      uint8_t *codes, int threads)
+{
+    if (!Y || T < 0 || E < 1 || k < 0 || k > E || ldY < E) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !inv)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int cb = (r + 1) / 2;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const uint16_t *y = Y + t * ldY;
+        for (int p = 0; p < k; ++p) outl[t * k + p] = y[idx_sorted[p]];
+        uint8_t *row = codes ? codes + t * cb : NULL;
+        if (row) memset(row, 0, (size_t)cb);
+        for (int c = 0; c < r; ++c) {
+            int j = comp[c];
+            float x = bf16_to_f32(y[j]);
+            float p = x * inv[j];
+            float q = rintf(p); /* ties to even */
+            if (q < -8.0f) q = -8.0f;
+            if (q > 7.0f) q = 7.0f;
+            unsigned nib = (unsigned)((int)q + 8);
+            if (c & 1)
+                row[c >> 1] |= (uint8_t)(nib << 4);
+            else
+                row[c >> 1] |= (uint8_t)nib;
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/*
+ * N static-mode messages -> out [T][E] in original feature order; step is
+ * float [N][E] in feature order.  Accumulation as in orc_decode_reduce.
+ */
+int orc_decode_reduce_static(int N, int64_t T, int E, int k, const int32_t *idx_sorted,
+                             const uint8_t *const *codes, const uint16_t *const *outl,
+                             const float *step, int accum, int out_fp32, void *out,
+                             int threads)
+{
+    if (N < 1 || T < 0 || E < 1 || k < 0 || k > E || !out) return ORC_ERR_ARG;
+    if (accum != ORC_ACC_FP32 && accum != ORC_ACC_BF16) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !step)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int cb = (r + 1) / 2;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float *of = out_fp32 ? (float *)out + t * E : NULL;
+        uint16_t *ob = out_fp32 ? NULL : (uint16_t *)out + t * E;
+        for (int col = 0; col < E; ++col) {
+            int is_outlier = col >= r;
+            int j = is_outlier ? idx_sorted[col - r] : comp[col];
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                float x;
+                if (is_outlier) {
+                    x = bf16_to_f32(outl[i][t * k + (col - r)]);
+                } else {
+                    uint8_t byte = codes[i][t * cb + (col >> 1)];
+                    unsigned nib = (col & 1) ? (byte >> 4) : (byte & 0x0Fu);
+                    float q = (float)((int)nib - 8);
+                    x = q * step[(int64_t)i * E + j];
                 }
                 if (accum == ORC_ACC_BF16) {
                     x = round_to_bf16(x);
