@@ -173,6 +173,37 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
                       int accum, int out_dtype, void *out, int64_t ldOut,
                       void *stream);
 
+/* ---- static symmetric mode (the paper's own quantiser, Sec. 3) --------------
+ * "Calibration": every feature on every device has static, independent
+ * quantisation parameters; "Selecting High Precision Features": the range is
+ * R = 2*max(-m, M) and every feature that is not kept in BF16 is symmetrically
+ * quantised to Int4.  The paper gives neither the step nor the code set; this
+ * library takes step = R/15 (fp32, IEEE), code = round-half-even of
+ * x * (1/step) clamped to -8..7, x_hat = code * step.  A feature whose
+ * calibrated range vanishes (step < 1e-30) is sent as code 0 and comes back as 0.
+ * The message is the codes section (same layout; the nibble is code + 8) and the
+ * outl section: nothing else travels, 4 + 12k/E bits per value.
+ *
+ * tpq_static_params turns the calibration state into the two tables the kernels
+ * read, in the compacted feature order of `plan`:
+ *   m, M         [device] fp32 [n_ranks][E] (as left by tpq_calibrate)
+ *   step, inv    [device] fp32 [n_ranks][tpq_static_table_floats(L)], 16-byte
+ *                aligned; entry c of a row belongs to the c-th feature that is not
+ *                selected, entries past r are 0
+ * tpq_encode_static / tpq_decode_reduce_static mirror tpq_encode /
+ * tpq_decode_reduce; `inv` / `step` point at the row of the first of the n_ranks
+ * devices handed over (rows of consecutive devices follow each other). */
+size_t tpq_static_table_floats(const tpq_layout *L);
+int tpq_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
+                      int n_ranks, float *step, float *inv, void *stream);
+int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *const *Y,
+                      int64_t ldY, int n_ranks, int64_t T, const float *inv,
+                      uint8_t *const *codes, uint16_t *const *outl, void *stream);
+int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
+                             const uint8_t *const *codes, const uint16_t *const *outl,
+                             const float *step, int accum, int out_dtype, void *out,
+                             int64_t ldOut, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

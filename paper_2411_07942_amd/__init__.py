@@ -33,6 +33,7 @@ EXPORTS = [
     "tpq_calibrate_workspace_bytes", "tpq_calibrate",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
     "tpq_encode", "tpq_decode_reduce",
+    "tpq_static_table_floats", "tpq_static_params", "tpq_encode_static", "tpq_decode_reduce_static",
 ]
 
 
@@ -88,6 +89,11 @@ def _load():
     lib.tpq_calibrate_finalize.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.tpq_encode.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, vp]
     lib.tpq_decode_reduce.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, c_int, c_int, vp, i64, vp]
+    lib.tpq_static_table_floats.argtypes = [LP]
+    lib.tpq_static_table_floats.restype = sz
+    lib.tpq_static_params.argtypes = [LP, vp, vp, vp, c_int, vp, vp, vp]
+    lib.tpq_encode_static.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp]
+    lib.tpq_decode_reduce_static.argtypes = [LP, vp, c_int, i64, vp, vp, vp, c_int, c_int, vp, i64, vp]
     _lib = lib
     return lib
 
@@ -269,3 +275,74 @@ def decode_reduce(L: Layout, plan: torch.Tensor, msgs: Sequence[Message], out: t
                   accum: int = ACC_FP32, stream=None) -> None:
     """Dequantise and add msgs[0..n-1] into out ([T,E] bf16 or fp32)."""
     decode_reduce_call(L, plan, msgs, out, accum)(stream)
+
+
+# ---- static symmetric mode -------------------------------------------------------
+
+def static_table_floats(L: Layout) -> int:
+    return int(_load().tpq_static_table_floats(ctypes.byref(L)))
+
+
+def static_params(L: Layout, plan: torch.Tensor, m: torch.Tensor, M: torch.Tensor,
+                  stream=None):
+    """Calibration state m, M (fp32 [n_ranks, E]) -> (step, inv), fp32
+    [n_ranks, static_table_floats(L)] in the plan's compacted feature order."""
+    assert m.dtype == torch.float32 and M.dtype == torch.float32 and m.shape == M.shape
+    assert m.is_contiguous() and M.is_contiguous() and m.shape[1] == L.E
+    n = m.shape[0]
+    w = max(static_table_floats(L), 4)
+    step = torch.empty((n, w), dtype=torch.float32, device=m.device)
+    inv = torch.empty((n, w), dtype=torch.float32, device=m.device)
+    _check(_load().tpq_static_params(ctypes.byref(L), _ptr(plan), _ptr(m), _ptr(M), n,
+                                     _ptr(step), _ptr(inv), _stream(stream)), "tpq_static_params")
+    return step, inv
+
+
+def encode_static_call(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor],
+                       inv: torch.Tensor, msgs: Sequence[Message]):
+    """Marshal a tpq_encode_static call once (inv: the rows of the ranks in Y, in order);
+    the returned function(stream=None) issues it."""
+    lib = _load()
+    n = len(Y)
+    T = Y[0].shape[0]
+    ldY = Y[0].stride(0) if T > 1 else max(L.E, Y[0].stride(0))
+    for y in Y:
+        assert y.dtype == torch.bfloat16 and y.shape == Y[0].shape and y.stride(1) == 1
+        assert T <= 1 or y.stride(0) == ldY
+    assert inv.dtype == torch.float32 and inv.is_contiguous() and inv.shape[0] >= n
+    args = (ctypes.byref(L), _ptr(plan), _ptr_array(Y, n), ldY, n, T, _ptr(inv),
+            _ptr_array([m.codes for m in msgs], n), _ptr_array([m.outl for m in msgs], n))
+    keep = (L, plan, list(Y), inv, list(msgs))
+
+    def call(stream=None, _keep=keep):
+        _check(lib.tpq_encode_static(*args, _stream(stream)), "tpq_encode_static")
+    return call
+
+
+def encode_static(L, plan, Y, inv, msgs, stream=None) -> None:
+    encode_static_call(L, plan, Y, inv, msgs)(stream)
+
+
+def decode_reduce_static_call(L: Layout, plan: torch.Tensor, msgs: Sequence[Message],
+                              step: torch.Tensor, out: torch.Tensor, accum: int = ACC_FP32):
+    """Marshal a tpq_decode_reduce_static call once; the returned function(stream=None)
+    issues it."""
+    lib = _load()
+    n = len(msgs)
+    T = out.shape[0]
+    out_dtype = OUT_FP32 if out.dtype == torch.float32 else OUT_BF16
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    assert step.dtype == torch.float32 and step.is_contiguous() and step.shape[0] >= n
+    ldOut = out.stride(0) if T > 1 else max(L.E, out.stride(0))
+    args = (ctypes.byref(L), _ptr(plan), n, T,
+            _ptr_array([m.codes for m in msgs], n), _ptr_array([m.outl for m in msgs], n),
+            _ptr(step), accum, out_dtype, _ptr(out), ldOut)
+    keep = (L, plan, list(msgs), step, out)
+
+    def call(stream=None, _keep=keep):
+        _check(lib.tpq_decode_reduce_static(*args, _stream(stream)), "tpq_decode_reduce_static")
+    return call
+
+
+def decode_reduce_static(L, plan, msgs, step, out, accum: int = ACC_FP32, stream=None) -> None:
+    decode_reduce_static_call(L, plan, msgs, step, out, accum)(stream)

@@ -264,4 +264,95 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
     return launch_decode(a, pc, ps, pz, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
 
+// ---- static symmetric mode ----------------------------------------------------
+
+size_t tpq_static_table_floats(const tpq_layout *L)
+{
+    if (check_layout(L)) return 0;
+    return static_cast<size_t>(8) * chunks_padded_of(L->r);
+}
+
+int tpq_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
+                      int n_ranks, float *step, float *inv, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS) return TPQ_ERR_SHAPE;
+    if (L->r == 0) return TPQ_OK;
+    if (!plan || !m || !M || !step || !inv) return TPQ_ERR_NULL;
+    if (!aligned16(plan) || !aligned16(step) || !aligned16(inv)) return TPQ_ERR_ALIGN;
+    return launch_static_params(L, plan, m, M, n_ranks, step, inv, static_cast<hipStream_t>(stream));
+}
+
+int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *const *Y,
+                      int64_t ldY, int n_ranks, int64_t T, const float *inv,
+                      uint8_t *const *codes, uint16_t *const *outl, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldY < L->E) return TPQ_ERR_SHAPE;
+    if (T * n_ranks > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
+    if ((ldY % 8) != 0) return TPQ_ERR_ALIGN;
+    if (!plan) return TPQ_ERR_NULL;
+    if (!aligned16(plan)) return TPQ_ERR_ALIGN;
+    RankPtrs pY, pc, po, none;
+    memset(&none, 0, sizeof none);
+    const bool quant = L->r > 0, keep = L->k > 0;
+    if (quant && !inv) return TPQ_ERR_NULL;
+    if (quant && !aligned16(inv)) return TPQ_ERR_ALIGN;
+    if ((rc = gather_ptrs(pY, reinterpret_cast<const void *const *>(Y), n_ranks, true))) return rc;
+    if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
+    if (T == 0) return TPQ_OK;
+    EncodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldY = ldY;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.inv_c = inv;
+    a.static_stride = 8 * a.chunks_padded;
+    return launch_encode(a, pY, pc, none, none, po, static_cast<hipStream_t>(stream));
+}
+
+int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
+                             const uint8_t *const *codes, const uint16_t *const *outl,
+                             const float *step, int accum, int out_dtype, void *out,
+                             int64_t ldOut, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
+    if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
+    if (T > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
+    if ((ldOut % (out_dtype == TPQ_OUT_FP32 ? 4 : 8)) != 0) return TPQ_ERR_ALIGN;
+    if (!plan || !out) return TPQ_ERR_NULL;
+    if (!aligned16(plan) || !aligned16(out)) return TPQ_ERR_ALIGN;
+    RankPtrs pc, po, none;
+    memset(&none, 0, sizeof none);
+    const bool quant = L->r > 0, keep = L->k > 0;
+    if (quant && !step) return TPQ_ERR_NULL;
+    if (quant && !aligned16(step)) return TPQ_ERR_ALIGN;
+    if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
+    if (T == 0) return TPQ_OK;
+    DecodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldOut = ldOut;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.out = out;
+    a.step_c = quant ? step : nullptr;
+    a.static_stride = 8 * a.chunks_padded;
+    return launch_decode(a, pc, none, none, po, accum, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -54,6 +54,11 @@ __device__ __forceinline__ void accumulate8(float (&acc)[8], float (&x)[8], bool
 // Outlier wave: lane p adds the ranks' bf16 values of outlier p and stores the sum at
 // its column.
 // grid: x = row, y = groups of 4 waves.
+//
+// LPG == 0 selects the static symmetric mode (Sec. 3): no scale / zero sections; a
+// feature's value is (nibble - 8) * step, the steps of (device, feature) read from a
+// table in compacted order (8 per chunk and device: two 128-bit loads that the L2
+// serves, the table being shared by every row).
 // ---------------------------------------------------------------------------
 template <int LPG, int ACC, int OUT>
 __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs codesp, RankPtrs scalep,
@@ -113,7 +118,8 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
     const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
     const uint32_t chunk = task * 64u + lane;
-    const uint32_t g = min(chunk / LPG, ng - 1u);
+    constexpr bool STATIC = LPG == 0;
+    const uint32_t g = STATIC ? 0u : min(chunk / (STATIC ? 1u : LPG), ng - 1u);
     // One 32-bit byte offset per section serves every rank (the host keeps
     // T * pitch below 2^31 per launch): the rank only changes the scalar base.
     const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
@@ -157,9 +163,46 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
             }
         }
     };
+    // static mode, 4 ranks at a time: a code word and 8 steps each
+    auto batch_static = [&](uint32_t i0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        uint32_t w[4];
+        float4 sa[4], sb[4];
+        const void *const *pc = codesp.p + i0;
+        const float *tab = a.step_c + 8u * chunk;  // chunk < chunks_padded: inside the row
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
+            w[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                static_cast<const uint8_t *>(pc[i]) + off_codes));
+            const float *row = tab + static_cast<int64_t>(i0 + i) * a.static_stride;
+            sa[j] = *reinterpret_cast<const float4 *>(row);
+            sb[j] = *reinterpret_cast<const float4 *>(row + 4);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (FULL || i0 + j < N) {  // uniform
+                uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
+                asm volatile("" : "+v"(lo), "+v"(hi));
+                const float st[8] = {sa[j].x, sa[j].y, sa[j].z, sa[j].w, sb[j].x, sb[j].y, sb[j].z, sb[j].w};
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
+                    x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
+                }
+                accumulate8<ACC>(acc, x, i0 + j == 0);
+            }
+        }
+    };
     uint32_t i0 = 0;
-    for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
-    if (i0 < N) batch(i0, std::false_type{});
+    if constexpr (STATIC) {
+        for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
+        if (i0 < N) batch_static(i0, std::false_type{});
+    } else {
+        for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
+        if (i0 < N) batch(i0, std::false_type{});
+    }
     if (chunk >= chunks) return;
 
     uint32_t o[8];  // the 8 results as output words (bf16: two per word)
@@ -243,7 +286,8 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
         else                                                                                 \
             TPQ_LAUNCH3(LPG, TPQ_ACC_BF16, TPQ_OUT_FP32);                                    \
     } while (0)
-        switch (lpg) {
+        switch (a.step_c ? 0 : lpg) {
+        case 0: TPQ_LAUNCH2(0); break;  // static symmetric mode
         case 4: TPQ_LAUNCH2(4); break;
         case 8: TPQ_LAUNCH2(8); break;
         case 16: TPQ_LAUNCH2(16); break;

@@ -88,7 +88,12 @@ struct DirectOcc {  // waves per SIMD the register budget is set for
     static constexpr int value = 8;
 };
 
-template <int LPG, int P>
+//
+// STATIC selects the static symmetric mode (Sec. 3, "Calibration" and "Selecting High
+// Precision Features"): the reciprocal step of every (device, feature) comes from a
+// table in compacted order, nothing is measured per group, and only codes and selected
+// features are written.  Everything up to the features in registers is shared.
+template <int LPG, int P, bool STATIC>
 __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     EncodeArgs a, RankPtrs Yp, RankPtrs codesp, RankPtrs scalep, RankPtrs zerop, RankPtrs outlp)
 {
@@ -152,7 +157,7 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     if (ln < n_q) win_b = *reinterpret_cast<const u32x4_a4 *>(yrow + (slot8.y & 0x1FFFFu));
     if (64u + ln < n_q) win_b2 = *reinterpret_cast<const u32x4_a4 *>(yrow + (rec2.y & 0x1FFFFu));
 
-    constexpr int GPS = 64 * P / LPG;  // groups per segment
+    constexpr int GPS = STATIC ? 0 : 64 * P / (STATIC ? 1 : LPG);  // groups per segment
     extern __shared__ u32x4 smem_direct[];
     uint8_t *slots = reinterpret_cast<uint8_t *>(smem_direct) + wave * (32u * a.patch_slots + 4u * GPS);
     uint32_t *l_meta = reinterpret_cast<uint32_t *>(slots + 32u * a.patch_slots);
@@ -237,141 +242,175 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     for (int p = 0; p < P; ++p)
         if (d[p] & kDir16Slot) v[p] = *reinterpret_cast<const u32x4 *>(slots + 32u * my_slot[p]);
 
-    // D: group min / max.  The upper feature of a word is compared as the whole
-    // word: as a float the word lies between that feature and its successor in
-    // magnitude, so it wins exactly where the feature would, and masking the
-    // winner's low half gives the feature itself.  After the DPP reduction every
-    // lane of a group holds the group's range.
-    float mn[P], mx[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const float l0 = bf16_lo_to_f32(v[p].x), l1 = bf16_lo_to_f32(v[p].y);
-        const float l2 = bf16_lo_to_f32(v[p].z), l3 = bf16_lo_to_f32(v[p].w);
-        const float h0 = __uint_as_float(v[p].x), h1 = __uint_as_float(v[p].y);
-        const float h2 = __uint_as_float(v[p].z), h3 = __uint_as_float(v[p].w);
-        const float lo = fminf(fminf(fminf(l0, l1), fminf(l2, l3)),
-                               fminf(fminf(h0, h1), fminf(h2, h3)));
-        const float hi = fmaxf(fmaxf(fmaxf(l0, l1), fmaxf(l2, l3)),
-                               fmaxf(fmaxf(h0, h1), fmaxf(h2, h3)));
-        mn[p] = __uint_as_float(__float_as_uint(lo) & 0xFFFF0000u);
-        mx[p] = __uint_as_float(__float_as_uint(hi) & 0xFFFF0000u);
-    }
-    if (last_seg) {
-        // chunks beyond the row must not touch their group's range
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            if ((pass0 + p) * 64u + ln >= static_cast<uint32_t>(a.chunks)) {
-                mn[p] = 3.3895314e38f;   // the largest finite bf16
-                mx[p] = -3.3895314e38f;
-            }
-        }
-    }
-    group_minmax_n<LPG, P>(mn, mx);
-
-    // E: zero, bf16 scale and its reciprocal, in every lane (cheaper than a trip
-    // through LDS to one lane per group).  Both divisions are exact replacements of
-    // the IEEE ones: x / 15 as x * fl(1/15) with one fused correction step (equal
-    // to the correctly rounded quotient for every float), 1 / scale as the hardware
-    // reciprocal with one Newton step (equal to the correctly rounded reciprocal
-    // for every bf16 scale whose reciprocal is a normal number, which covers every
-    // finite range).  Each group's first lane parks (scale | zero << 16) in LDS, from
-    // where lane g stores group g's pair.
-    float inv[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        mn[p] = mn[p] + 0.0f;  // a zero minimum is stored as +0
-        const float span = mx[p] - mn[p];
-        const float s32 = div_by_15(span);
-        const uint32_t sb = pack_bf16x2(s32, s32) & 0xFFFFu;
-        const float s = bf16_bits_to_f32(sb);
-        const bool constant = s < 1e-30f;
-        inv[p] = constant ? 0.0f : reciprocal_of_scale(s);
-        if ((ln % LPG) == 0)
-            l_meta[p * (64 / LPG) + ln / LPG] = (constant ? 0u : sb) | (__float_as_uint(mn[p]) & 0xFFFF0000u);
-    }
-    wave_lds_fence();
-    {
-        uint16_t *scale = reinterpret_cast<uint16_t *>(
-            static_cast<uint8_t *>(const_cast<void *>(scalep.p[rank])) +
-            static_cast<int64_t>(t) * a.pitch_meta);
-        uint16_t *zero = reinterpret_cast<uint16_t *>(
-            static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
-            static_cast<int64_t>(t) * a.pitch_meta);
-        const uint32_t g0 = pass0 * (64 / LPG);
-        if (GPS <= 32) {
-            // one store instruction for both: lanes 0..31 scales, lanes 32..63 zeros
-            const uint32_t gl = ln & 31u;
-            const bool is_zero = ln >= 32u;
-            if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
-                const uint32_t m = l_meta[gl];
-                (is_zero ? zero : scale)[g0 + gl] = static_cast<uint16_t>(is_zero ? m >> 16 : m & 0xFFFFu);
-            }
-        } else {
-#pragma unroll
-            for (uint32_t gl0 = 0; gl0 < static_cast<uint32_t>(GPS); gl0 += 64) {
-                const uint32_t gl = gl0 + ln;
-                if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
-                    const uint32_t m = l_meta[gl];
-                    scale[g0 + gl] = static_cast<uint16_t>(m & 0xFFFFu);
-                    zero[g0 + gl] = static_cast<uint16_t>(m >> 16);
-                }
-            }
-        }
-    }
-
-    // F: quantise and pack.  (x - zero) * inv lies in [0, 15.06] for finite input
-    // (scale is (max - min) / 15 rounded to 8 significant bits), so the rounded
-    // value is a 4-bit code without a clamp.  The float -> byte conversion rounds
-    // to the nearest even integer and drops the result into a byte of its
-    // destination; the codes of a feature pair land swapped in neighbouring bytes,
-    // so that (a << 12) | a joins each pair into one byte, and a byte permute
-    // collects the four bytes.
     uint32_t *codes = reinterpret_cast<uint32_t *>(
         static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
         static_cast<int64_t>(t) * a.pitch_codes);
+    uint32_t w[P];
+    if constexpr (STATIC) {
+        // code = clamp(rint(x * inv), -8, 7), sent as code + 8.  The product is rounded
+        // to fp32 before the integer rounding (a fused multiply-add would round once
+        // and differ at near-ties).  Adding 1.5 * 2^23 + 8 to the clamped product leaves
+        // rint(.) + 8 in the sum's low byte: the sum's unit in the last place is 1, the
+        // addition rounds to nearest even, and the offset is even, so ties fall as rint's.
+        const float *invr = a.inv_c + static_cast<int64_t>(rank) * a.static_stride;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t chunk = (pass0 + p) * 64u + ln;  // < chunks_padded: inside the table
+            const float4 ia = *reinterpret_cast<const float4 *>(invr + 8u * chunk);
+            const float4 ib = *reinterpret_cast<const float4 *>(invr + 8u * chunk + 4u);
+            const float iv[8] = {ia.x, ia.y, ia.z, ia.w, ib.x, ib.y, ib.z, ib.w};
+            const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+            uint32_t by[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float x0 = bf16_lo_to_f32(wv[e2]), x1 = bf16_hi_to_f32(wv[e2]);
+                const float c0 = __builtin_amdgcn_fmed3f(x0 * iv[2 * e2], -8.0f, 7.0f);
+                const float c1 = __builtin_amdgcn_fmed3f(x1 * iv[2 * e2 + 1], -8.0f, 7.0f);
+                const uint32_t n0 = __float_as_uint(c0 + 12582920.0f);
+                const uint32_t n1 = __float_as_uint(c1 + 12582920.0f);
+                by[e2] = (n1 << 4) | n0;  // low byte: the pair's two nibbles
+            }
+            const uint32_t lo = __builtin_amdgcn_perm(by[1], by[0], 0x00000400u);
+            const uint32_t hi = __builtin_amdgcn_perm(by[3], by[2], 0x00000400u);
+            w[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+    } else {
+        // D: group min / max.  The upper feature of a word is compared as the whole
+        // word: as a float the word lies between that feature and its successor in
+        // magnitude, so it wins exactly where the feature would, and masking the
+        // winner's low half gives the feature itself.  After the DPP reduction every
+        // lane of a group holds the group's range.
+        float mn[P], mx[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const float l0 = bf16_lo_to_f32(v[p].x), l1 = bf16_lo_to_f32(v[p].y);
+            const float l2 = bf16_lo_to_f32(v[p].z), l3 = bf16_lo_to_f32(v[p].w);
+            const float h0 = __uint_as_float(v[p].x), h1 = __uint_as_float(v[p].y);
+            const float h2 = __uint_as_float(v[p].z), h3 = __uint_as_float(v[p].w);
+            const float lo = fminf(fminf(fminf(l0, l1), fminf(l2, l3)),
+                                   fminf(fminf(h0, h1), fminf(h2, h3)));
+            const float hi = fmaxf(fmaxf(fmaxf(l0, l1), fmaxf(l2, l3)),
+                                   fmaxf(fmaxf(h0, h1), fmaxf(h2, h3)));
+            mn[p] = __uint_as_float(__float_as_uint(lo) & 0xFFFF0000u);
+            mx[p] = __uint_as_float(__float_as_uint(hi) & 0xFFFF0000u);
+        }
+        if (last_seg) {
+            // chunks beyond the row must not touch their group's range
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                if ((pass0 + p) * 64u + ln >= static_cast<uint32_t>(a.chunks)) {
+                    mn[p] = 3.3895314e38f;   // the largest finite bf16
+                    mx[p] = -3.3895314e38f;
+                }
+            }
+        }
+        group_minmax_n<LPG, P>(mn, mx);
+
+        // E: zero, bf16 scale and its reciprocal, in every lane (cheaper than a trip
+        // through LDS to one lane per group).  Both divisions are exact replacements of
+        // the IEEE ones: x / 15 as x * fl(1/15) with one fused correction step (equal
+        // to the correctly rounded quotient for every float), 1 / scale as the hardware
+        // reciprocal with one Newton step (equal to the correctly rounded reciprocal
+        // for every bf16 scale whose reciprocal is a normal number, which covers every
+        // finite range).  Each group's first lane parks (scale | zero << 16) in LDS, from
+        // where lane g stores group g's pair.
+        float inv[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            mn[p] = mn[p] + 0.0f;  // a zero minimum is stored as +0
+            const float span = mx[p] - mn[p];
+            const float s32 = div_by_15(span);
+            const uint32_t sb = pack_bf16x2(s32, s32) & 0xFFFFu;
+            const float s = bf16_bits_to_f32(sb);
+            const bool constant = s < 1e-30f;
+            inv[p] = constant ? 0.0f : reciprocal_of_scale(s);
+            if ((ln % LPG) == 0)
+                l_meta[p * (64 / LPG) + ln / LPG] = (constant ? 0u : sb) | (__float_as_uint(mn[p]) & 0xFFFF0000u);
+        }
+        wave_lds_fence();
+        {
+            uint16_t *scale = reinterpret_cast<uint16_t *>(
+                static_cast<uint8_t *>(const_cast<void *>(scalep.p[rank])) +
+                static_cast<int64_t>(t) * a.pitch_meta);
+            uint16_t *zero = reinterpret_cast<uint16_t *>(
+                static_cast<uint8_t *>(const_cast<void *>(zerop.p[rank])) +
+                static_cast<int64_t>(t) * a.pitch_meta);
+            const uint32_t g0 = pass0 * (64 / LPG);
+            if (GPS <= 32) {
+                // one store instruction for both: lanes 0..31 scales, lanes 32..63 zeros
+                const uint32_t gl = ln & 31u;
+                const bool is_zero = ln >= 32u;
+                if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
+                    const uint32_t m = l_meta[gl];
+                    (is_zero ? zero : scale)[g0 + gl] = static_cast<uint16_t>(is_zero ? m >> 16 : m & 0xFFFFu);
+                }
+            } else {
+#pragma unroll
+                for (uint32_t gl0 = 0; gl0 < static_cast<uint32_t>(GPS); gl0 += 64) {
+                    const uint32_t gl = gl0 + ln;
+                    if (gl < static_cast<uint32_t>(GPS) && g0 + gl < static_cast<uint32_t>(a.ng)) {
+                        const uint32_t m = l_meta[gl];
+                        scale[g0 + gl] = static_cast<uint16_t>(m & 0xFFFFu);
+                        zero[g0 + gl] = static_cast<uint16_t>(m >> 16);
+                    }
+                }
+            }
+        }
+
+        // F: quantise and pack.  (x - zero) * inv lies in [0, 15.06] for finite input
+        // (scale is (max - min) / 15 rounded to 8 significant bits), so the rounded
+        // value is a 4-bit code without a clamp.  The float -> byte conversion rounds
+        // to the nearest even integer and drops the result into a byte of its
+        // destination; the codes of a feature pair land swapped in neighbouring bytes,
+        // so that (a << 12) | a joins each pair into one byte, and a byte permute
+        // collects the four bytes.
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+            uint32_t h[2];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float pr[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t word = wv[half * 2 + (e >> 1)];
+                    const float x = (e & 1) ? bf16_hi_to_f32(word) : bf16_lo_to_f32(word);
+                    const float df = x - mn[p];
+                    pr[e] = df * inv[p];
+                }
+                uint32_t b = __builtin_amdgcn_cvt_pk_u8_f32(pr[1], 0u, 0u);
+                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[0], 1u, b);
+                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[3], 2u, b);
+                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[2], 3u, b);
+                h[half] = (b << 12) | b;
+            }
+            w[p] = __builtin_amdgcn_perm(h[1], h[0], 0x07050301u);
+        }
+    }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
-        uint32_t h[2];
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            float pr[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t word = wv[half * 2 + (e >> 1)];
-                const float x = (e & 1) ? bf16_hi_to_f32(word) : bf16_lo_to_f32(word);
-                const float df = x - mn[p];
-                pr[e] = df * inv[p];
-            }
-            uint32_t b = __builtin_amdgcn_cvt_pk_u8_f32(pr[1], 0u, 0u);
-            b = __builtin_amdgcn_cvt_pk_u8_f32(pr[0], 1u, b);
-            b = __builtin_amdgcn_cvt_pk_u8_f32(pr[3], 2u, b);
-            b = __builtin_amdgcn_cvt_pk_u8_f32(pr[2], 3u, b);
-            h[half] = (b << 12) | b;
-        }
-        uint32_t w = __builtin_amdgcn_perm(h[1], h[0], 0x07050301u);
         const uint32_t chunk = (pass0 + p) * 64u + ln;
         if (last_seg) {
             const int n_valid = a.r - 8 * static_cast<int>(chunk);
-            if (n_valid < 8) w &= (1u << (4 * (n_valid & 7))) - 1u;
-            if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w, codes + chunk);
+            if (n_valid < 8) w[p] &= (1u << (4 * (n_valid & 7))) - 1u;
+            if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w[p], codes + chunk);
         } else {
-            __builtin_nontemporal_store(w, codes + chunk);
+            __builtin_nontemporal_store(w[p], codes + chunk);
         }
     }
 }
 
-template <int LPG, int P>
+template <int LPG, int P, bool STATIC>
 static hipError_t launch_direct_lp(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                                    const RankPtrs &scale, const RankPtrs &zero,
                                    const RankPtrs &outl, size_t lds, dim3 grid, hipStream_t s)
 {
     hipError_t e = hipSuccess;
     if (lds > 65536)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
-    k_encode_direct<LPG, P><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl);
+    k_encode_direct<LPG, P, STATIC><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl);
     return hipGetLastError();
 }
 
@@ -400,7 +439,8 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         a.off_drec2 = o.drec2;
     }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
-    const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + 4u * (64 * P / lpg));
+    const bool is_static = a.inv_c != nullptr;
+    const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + (is_static ? 0u : 4u * (64 * P / lpg)));
 
     // task numbers of a rank stay below 2^32 / segs (the kernel divides by multiplying)
     // and the grid's x extent below 2^31: hand over the rows in blocks
@@ -412,21 +452,24 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         for (int i = 0; i < a.n_ranks; ++i) {
             Y.p[i] = static_cast<const uint8_t *>(Y.p[i]) + row0 * a.ldY * 2;
             codes.p[i] = static_cast<const uint8_t *>(codes.p[i]) + row0 * a.pitch_codes;
-            scale.p[i] = static_cast<const uint8_t *>(scale.p[i]) + row0 * a.pitch_meta;
-            zero.p[i] = static_cast<const uint8_t *>(zero.p[i]) + row0 * a.pitch_meta;
+            if (scale.p[i]) scale.p[i] = static_cast<const uint8_t *>(scale.p[i]) + row0 * a.pitch_meta;
+            if (zero.p[i]) zero.p[i] = static_cast<const uint8_t *>(zero.p[i]) + row0 * a.pitch_meta;
             if (outl.p[i]) outl.p[i] = static_cast<const uint8_t *>(outl.p[i]) + row0 * a.pitch_outl;
         }
         a.n_tasks = a.T * a.segs;  // per rank
         const dim3 grid(static_cast<unsigned>((a.n_tasks + 3) / 4), static_cast<unsigned>(a.n_ranks));
-#define TPQ_DIRECT_P(LPG, PP) \
-    case PP: e = launch_direct_lp<LPG, PP>(a, Y, codes, scale, zero, outl, lds, grid, s); break;
+#define TPQ_DIRECT_P(LPG, PP)                                                                       \
+    case PP:                                                                                        \
+        e = launch_direct_lp<LPG, PP, LPG == 0>(a, Y, codes, scale, zero, outl, lds, grid, s);      \
+        break;
 #define TPQ_DIRECT(LPG)                                                                      \
     switch (P) {                                                                             \
         TPQ_DIRECT_P(LPG, 1) TPQ_DIRECT_P(LPG, 2) TPQ_DIRECT_P(LPG, 3) TPQ_DIRECT_P(LPG, 4)  \
         TPQ_DIRECT_P(LPG, 5)                                                                 \
     default: return hipErrorInvalidValue;                                                    \
     }
-        switch (lpg) {
+        switch (is_static ? 0 : lpg) {
+        case 0: TPQ_DIRECT(0) break;  // static symmetric mode: no groups
         case 4: TPQ_DIRECT(4) break;
         case 8: TPQ_DIRECT(8) break;
         case 16: TPQ_DIRECT(16) break;

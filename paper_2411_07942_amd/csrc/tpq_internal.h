@@ -216,6 +216,9 @@ struct EncodeArgs {
     int64_t n_tasks;  // T * segs (per rank)
     int32_t dslots;   // slots in the plan's tables of the direct kernel
     uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
+    // static symmetric mode: reciprocal steps, fp32 [n_ranks][static_stride] in compacted order
+    const float *inv_c;
+    int32_t static_stride;
     // byte offsets of the plan's tables (what the header holds, known to the host too)
     int32_t off_idx, off_dirr, off_dsel, off_dpos16, off_dslot8, off_dseg, off_drec, off_drec2;
 };
@@ -227,6 +230,9 @@ struct DecodeArgs {
     int64_t T, ldOut;
     int64_t pitch_codes, pitch_meta, pitch_outl;
     void *out;
+    // static symmetric mode: steps, fp32 [n_ranks][static_stride] in compacted order
+    const float *step_c;
+    int32_t static_stride;
 };
 
 // ---- host-side helpers --------------------------------------------------------
@@ -248,6 +254,8 @@ int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &sc
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
                          float gamma, float *m, float *M, float *ws, hipStream_t s);
 int calibrate_parts(int64_t S, int E);
+int launch_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
+                         int n_ranks, float *step, float *inv, hipStream_t s);
 int launch_finalize(const float *m, const float *M, int N, int E, int k, float *R,
                     float *Rbar, int32_t *idx_sorted, int32_t *idx_ranked, int32_t *ws,
                     hipStream_t s);

@@ -344,6 +344,43 @@ __global__ void k_plan_drec(uint8_t *plan, int chunks_padded, PlanOffsets o)
     rec2[3] = 0u;
 }
 
+// Static symmetric mode (Sec. 3): per device i and compacted position c (feature j =
+// src_of[c]): R = 2*max(-m, M), step = R/15, inv = 1/step; a vanishing range gives 0, 0.
+__global__ void k_static_params(const uint8_t *plan, const float *__restrict__ m,
+                                const float *__restrict__ M, int E, int r, int stride,
+                                float *__restrict__ step, float *__restrict__ inv)
+{
+    const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + h->src_offset);
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y;
+    if (c >= stride) return;
+    float d = 0.0f, v = 0.0f;
+    if (h->magic == kPlanMagic && h->status == kPlanOk && c < r) {
+        const int j = src[c];
+        const float lo = -m[static_cast<int64_t>(i) * E + j], hi = M[static_cast<int64_t>(i) * E + j];
+        float R = 2.0f * (lo > hi ? lo : hi);
+        R += 0.0f;
+        const float q = R / 15.0f;
+        if (q >= 1e-30f) {
+            d = q;
+            v = 1.0f / q;
+        }
+    }
+    step[static_cast<int64_t>(i) * stride + c] = d;
+    inv[static_cast<int64_t>(i) * stride + c] = v;
+}
+
+int launch_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
+                         int n_ranks, float *step, float *inv, hipStream_t s)
+{
+    const int stride = 8 * chunks_padded_of(L->r);
+    if (stride == 0) return TPQ_OK;
+    const dim3 grid((stride + 255) / 256, n_ranks);
+    k_static_params<<<grid, 256, 0, s>>>(static_cast<const uint8_t *>(plan), m, M, L->E, L->r, stride, step, inv);
+    return hip_result(hipGetLastError());
+}
+
 int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipStream_t s)
 {
     const int E = L->E, k = L->k, r = L->r;
