@@ -12,7 +12,10 @@ This script adds what a deployment asks next, one JSON line per section:
           over 8 messages, (a) launched back to back, (b) the same 184 launches replayed from one
           HIP graph (every replay is checked against the eager result);
   large   the large prefill stress block (16 ranks, [16384 x 8192]) in its four variants, fp32
-          accumulate, bf16 and fp32 output.
+          accumulate, bf16 and fp32 output;
+  static  the Llama-2-13B-shaped block in the static symmetric mode (per device and feature steps
+          from calibration; only codes and selected features travel): encode of all ranks, of one
+          rank, decode_reduce in both accumulate modes.
 
 Inputs are seeded synthetic activations (workloads/), resident in HBM before timing.  The selected
 features of each block are its planted outlier columns filled up to k with random other columns (a
@@ -170,15 +173,51 @@ def section_large(tpq, wl, args):
             "note": "16 ranks x [16384 x 8192], fp32 accumulate; one buffer set (5.6 GB, far beyond the caches)"}
 
 
+def section_static(tpq, wl, args):
+    w = wl.LLAMA_PREFILL
+    N, T, E = w.N, w.T, w.E
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
+    tpq.plan_check(L, plan)
+    sets = []
+    step = inv = None
+    for s in range(6):
+        Ys = wl.partial_sums(w, block=s, device=dev)
+        if step is None:   # ranges of the first block stand in for the calibration state
+            m = torch.stack([y.float().amin(0) for y in Ys]).contiguous()
+            M = torch.stack([y.float().amax(0) for y in Ys]).contiguous()
+            step, inv = tpq.static_params(L, plan, m, M)
+        msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+        out = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        sets.append(dict(enc=tpq.encode_static_call(L, plan, Ys, inv, msgs),
+                         enc1=tpq.encode_static_call(L, plan, Ys[:1], inv, msgs[:1]),
+                         dec_bf16=tpq.decode_reduce_static_call(L, plan, msgs, step, out, tpq.ACC_BF16),
+                         dec_fp32=tpq.decode_reduce_static_call(L, plan, msgs, step, out, tpq.ACC_FP32),
+                         keep=(Ys, msgs, out)))
+    W = L.code_bytes + 2 * L.k          # bytes per row that travel in this mode
+    B_enc, B_dec = N * T * (2 * E + W), T * (N * W + 2 * E)
+    t = {k: timed([s[k] for s in sets], 40) / len(sets) for k in ("enc", "enc1", "dec_bf16", "dec_fp32")}
+    share = (B_enc / N + B_dec) / ((t["enc1"] + t["dec_bf16"]) * 1e-6) / 1e9
+    return {"section": "llama2_13b_prefill_static_mode", "bits_per_value": round(8.0 * W / E, 4),
+            "us": {k: round(v, 2) for k, v in t.items()},
+            "encode_all_ranks_GBps": round(B_enc / t["enc"] / 1e3, 1),
+            "encode_one_rank_GBps": round(B_enc / N / t["enc1"] / 1e3, 1),
+            "decode_reduce_GBps": {"bf16": round(B_dec / t["dec_bf16"] / 1e3, 1), "fp32": round(B_dec / t["dec_fp32"] / 1e3, 1)},
+            "per_device_share_GBps": round(share, 1), "per_device_share_frac_of_peak": round(share / HBM_PEAK_GBS, 4),
+            "note": "algorithmic bytes exclude the step tables (160 KB per device, shared by all rows, served by L2)"}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sections", default="llama,gemma,large")
+    ap.add_argument("--sections", default="llama,gemma,large,static")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")
     import paper_2411_07942_amd as tpq
     import workloads as wl
-    table = {"llama": section_llama, "gemma": section_gemma, "large": section_large}
+    table = {"llama": section_llama, "gemma": section_gemma, "large": section_large,
+             "static": section_static}
     for name in args.sections.split(","):
         print(json.dumps(table[name](tpq, wl, args)), flush=True)
 

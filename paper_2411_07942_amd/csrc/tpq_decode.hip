@@ -54,20 +54,12 @@ __device__ __forceinline__ void accumulate8(float (&acc)[8], float (&x)[8], bool
 // Outlier wave: lane p adds the ranks' bf16 values of outlier p and stores the sum at
 // its column.
 // grid: x = row, y = groups of 4 waves.
-//
-// LPG == 0 selects the static symmetric mode (Sec. 3): no scale / zero sections; a
-// feature's value is (nibble - 8) * step, the steps of (device, feature) read from a
-// table in compacted order (8 per chunk and device: two 128-bit loads that the L2
-// serves, the table being shared by every row).
 // ---------------------------------------------------------------------------
 template <int LPG, int ACC, int OUT>
 __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs codesp, RankPtrs scalep,
                                                      RankPtrs zerop, RankPtrs outlp)
 {
-    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
-    if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
-        ph->G != a.G)
-        return;
+    if (plan_header_bad(a.plan, a.E, a.k, a.G)) return;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t t = blockIdx.x;
@@ -84,7 +76,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
         // ---- selected features ------------------------------------------------------
         const uint32_t p = (task - passes) * 64u + lane;
         if (p >= static_cast<uint32_t>(a.k)) return;
-        const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + ph->idx_offset);
+        const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + a.off_idx);
         const uint32_t off_outl = t * static_cast<uint32_t>(a.pitch_outl);
         const uint32_t j = static_cast<uint32_t>(idx[p]);
         float acc = 0.f;
@@ -115,11 +107,10 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     }
 
     // ---- one pass of quantised features ---------------------------------------------
-    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + ph->pos_offset);
-    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + ph->irr_src_offset);
+    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + a.off_pos);
+    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + a.off_irr_src);
     const uint32_t chunk = task * 64u + lane;
-    constexpr bool STATIC = LPG == 0;
-    const uint32_t g = STATIC ? 0u : min(chunk / (STATIC ? 1u : LPG), ng - 1u);
+    const uint32_t g = min(chunk / LPG, ng - 1u);
     // One 32-bit byte offset per section serves every rank (the host keeps
     // T * pitch below 2^31 per launch): the rank only changes the scalar base.
     const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
@@ -163,46 +154,9 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
             }
         }
     };
-    // static mode, 4 ranks at a time: a code word and 8 steps each
-    auto batch_static = [&](uint32_t i0, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;
-        uint32_t w[4];
-        float4 sa[4], sb[4];
-        const void *const *pc = codesp.p + i0;
-        const float *tab = a.step_c + 8u * chunk;  // chunk < chunks_padded: inside the row
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
-            w[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
-                static_cast<const uint8_t *>(pc[i]) + off_codes));
-            const float *row = tab + static_cast<int64_t>(i0 + i) * a.static_stride;
-            sa[j] = *reinterpret_cast<const float4 *>(row);
-            sb[j] = *reinterpret_cast<const float4 *>(row + 4);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (FULL || i0 + j < N) {  // uniform
-                uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
-                asm volatile("" : "+v"(lo), "+v"(hi));
-                const float st[8] = {sa[j].x, sa[j].y, sa[j].z, sa[j].w, sb[j].x, sb[j].y, sb[j].z, sb[j].w};
-                float x[8];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
-                    x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
-                }
-                accumulate8<ACC>(acc, x, i0 + j == 0);
-            }
-        }
-    };
     uint32_t i0 = 0;
-    if constexpr (STATIC) {
-        for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
-        if (i0 < N) batch_static(i0, std::false_type{});
-    } else {
-        for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
-        if (i0 < N) batch(i0, std::false_type{});
-    }
+    for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
+    if (i0 < N) batch(i0, std::false_type{});
     if (chunk >= chunks) return;
 
     uint32_t o[8];  // the 8 results as output words (bf16: two per word)
@@ -244,6 +198,207 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     }
 }
 
+// ---------------------------------------------------------------------------
+// Static symmetric mode (Sec. 3): no scale / zero sections; a feature's value is
+// (nibble - 8) * step, the steps of (device, feature) read from a table in compacted
+// order (8 per chunk and device: two 128-bit loads that the L2 serves).  Same wave
+// roles, loads, accumulation order and stores as k_decode_pass, but a wave takes R
+// consecutive rows: the rows share the step loads, which otherwise outnumber the code
+// loads two to one.  Rows past the end are read as the last row and not stored.
+// grid: x = block of R rows, y = groups of 4 waves.
+// ---------------------------------------------------------------------------
+template <int ACC, int OUT, int R>
+__global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs codesp, RankPtrs outlp)
+{
+    if (plan_header_bad(a.plan, a.E, a.k, a.G)) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t task = blockIdx.y * 4u + wave;
+
+    constexpr uint32_t OB = OUT == TPQ_OUT_FP32 ? 4u : 2u;  // bytes per output value
+    const uint32_t N = static_cast<uint32_t>(a.n_ranks);
+    const uint32_t chunks = static_cast<uint32_t>(a.chunks);
+    const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
+    // the wave's rows; rows past the end are read as the last row and not stored
+    const uint32_t t0 = blockIdx.x * static_cast<uint32_t>(R);
+    const uint32_t n_rows = min(static_cast<uint32_t>(R), static_cast<uint32_t>(a.T) - t0);
+    uint32_t tr[R];
+    uint8_t *out_row[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        tr[rr] = t0 + min(static_cast<uint32_t>(rr), n_rows - 1u);
+        out_row[rr] = static_cast<uint8_t *>(a.out) + static_cast<int64_t>(tr[rr]) * a.ldOut * OB;
+    }
+
+    if (task >= passes) {
+        // ---- selected features ------------------------------------------------------
+        const uint32_t p = (task - passes) * 64u + lane;
+        if (p >= static_cast<uint32_t>(a.k)) return;
+        const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + a.off_idx);
+        const uint32_t j = static_cast<uint32_t>(idx[p]);
+        float acc[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) acc[rr] = 0.f;
+        for (uint32_t i0 = 0; i0 < N; i0 += 8) {
+            uint32_t v[R][8];
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj)
+                    v[rr][jj] = reinterpret_cast<const uint16_t *>(
+                        static_cast<const uint8_t *>(outlp.p[min(i0 + jj, N - 1u)]) +
+                        tr[rr] * static_cast<uint32_t>(a.pitch_outl))[p];
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    if (i0 + jj < N) {
+                        const float x = bf16_bits_to_f32(v[rr][jj]);
+                        if (i0 + jj == 0) {
+                            acc[rr] = x;
+                        } else {
+                            acc[rr] = acc[rr] + x;
+                            if (ACC == TPQ_ACC_BF16) acc[rr] = bf16_lo_to_f32(pack_bf16x2(acc[rr], acc[rr]));
+                        }
+                    }
+                }
+        }
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            if (static_cast<uint32_t>(rr) < n_rows) {
+                if (OUT == TPQ_OUT_FP32)
+                    *reinterpret_cast<float *>(out_row[rr] + 4u * j) = acc[rr];
+                else
+                    *reinterpret_cast<uint16_t *>(out_row[rr] + 2u * j) =
+                        static_cast<uint16_t>(pack_bf16x2(acc[rr], acc[rr]));
+            }
+        }
+        return;
+    }
+
+    // ---- one pass of quantised features ---------------------------------------------
+    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + a.off_pos);
+    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + a.off_irr_src);
+    const uint32_t chunk = task * 64u + lane;
+    // One 32-bit byte offset per section and row serves every rank (the host keeps
+    // T * pitch below 2^31 per launch): the rank only changes the scalar base.
+    uint32_t off_codes[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr)
+        off_codes[rr] = tr[rr] * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
+    const uint32_t cp = cpos[chunk];
+    // a split chunk's 8 columns: fetched now, so that the load overlaps the others
+    u32x4 tab = {0u, 0u, 0u, 0u};
+    if (cp & kNotRegular) tab = *reinterpret_cast<const u32x4 *>(irr_src + 8u * ((cp >> 16) & 0x7FFFu));
+    float acc[R][8];
+
+    // static mode, 4 ranks at a time: a code word per row and 8 steps each
+    auto batch_static = [&](uint32_t i0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        uint32_t w[R][4];
+        float4 sa[4], sb[4];
+        const void *const *pc = codesp.p + i0;
+        const float *tab = a.step_c + 8u * chunk;  // chunk < chunks_padded: inside the row
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+                w[rr][j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                    static_cast<const uint8_t *>(pc[i]) + off_codes[rr]));
+            const float *row = tab + static_cast<int64_t>(i0 + i) * a.static_stride;
+            sa[j] = *reinterpret_cast<const float4 *>(row);
+            sb[j] = *reinterpret_cast<const float4 *>(row + 4);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (FULL || i0 + j < N) {  // uniform
+                const float st[8] = {sa[j].x, sa[j].y, sa[j].z, sa[j].w, sb[j].x, sb[j].y, sb[j].z, sb[j].w};
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    uint32_t lo = w[rr][j] & 0x0F0F0F0Fu, hi = (w[rr][j] >> 4) & 0x0F0F0F0Fu;
+                    asm volatile("" : "+v"(lo), "+v"(hi));
+                    float x[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
+                        x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
+                    }
+                    accumulate8<ACC>(acc[rr], x, i0 + j == 0);
+                }
+            }
+        }
+    };
+    uint32_t i0 = 0;
+    for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
+    if (i0 < N) batch_static(i0, std::false_type{});
+    if (chunk >= chunks) return;
+
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        if (static_cast<uint32_t>(rr) >= n_rows) break;  // uniform
+        uint32_t o[8];  // the 8 results as output words (bf16: two per word)
+        if (OUT == TPQ_OUT_FP32) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = __float_as_uint(acc[rr][e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[rr][2 * e], acc[rr][2 * e + 1]);
+        }
+        if (!(cp & kNotRegular)) {
+            const uint32_t col = cp & 0xFFFFu;
+            if (OUT == TPQ_OUT_FP32) {
+                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
+                                            reinterpret_cast<u32x4_a4 *>(out_row[rr] + 4u * col));
+                __builtin_nontemporal_store(u32x4{o[4], o[5], o[6], o[7]},
+                                            reinterpret_cast<u32x4_a4 *>(out_row[rr] + 4u * col + 16u));
+            } else {
+                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
+                                            reinterpret_cast<u32x4_a2 *>(out_row[rr] + 2u * col));
+            }
+        } else {
+            // split (or ragged last) chunk: one store per feature
+            const uint32_t col[8] = {tab.x & 0xFFFFu, tab.x >> 16, tab.y & 0xFFFFu, tab.y >> 16,
+                                     tab.z & 0xFFFFu, tab.z >> 16, tab.w & 0xFFFFu, tab.w >> 16};
+            const int n_valid = a.r - 8 * static_cast<int>(chunk);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (e < n_valid) {
+                    if (OUT == TPQ_OUT_FP32)
+                        *reinterpret_cast<uint32_t *>(out_row[rr] + 4u * col[e]) = o[e];
+                    else
+                        *reinterpret_cast<uint16_t *>(out_row[rr] + 2u * col[e]) =
+                            static_cast<uint16_t>((e & 1) ? (o[e >> 1] >> 16) : (o[e >> 1] & 0xFFFFu));
+                }
+            }
+        }
+    }
+}
+
+#ifndef TPQ_STATIC_RPW
+#define TPQ_STATIC_RPW 4
+#endif
+// Rows per wave.  Static mode: 4 once the launch fills the machine (the rows share the
+// step table's loads); dynamic mode: 1 (measured: more rows per wave gain nothing there).
+static int rows_per_wave(bool is_static, int64_t T, int tasks)
+{
+    return (is_static && T * tasks >= 2 * 8192) ? TPQ_STATIC_RPW : 1;
+}
+
+template <int LPG, int ACC, int OUT>
+static void launch_rows(int rpw, dim3 grid, hipStream_t s, const DecodeArgs &a, const RankPtrs &codes,
+                        const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl)
+{
+    if constexpr (LPG == 0) {
+        if (rpw == 4)
+            k_decode_static<ACC, OUT, 4><<<grid, 256, 0, s>>>(a, codes, outl);
+        else
+            k_decode_static<ACC, OUT, 1><<<grid, 256, 0, s>>>(a, codes, outl);
+    } else {
+        k_decode_pass<LPG, ACC, OUT><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+    }
+}
+
 int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPtrs &scale_in,
                   const RankPtrs &zero_in, const RankPtrs &outl_in, int accum, int out_dtype,
                   hipStream_t s)
@@ -263,6 +418,12 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
     hipError_t e = hipSuccess;
     for (int64_t row0 = 0; row0 < a_in.T && e == hipSuccess; row0 += rows_per_launch) {
         DecodeArgs a = a_in;
+        {
+            const PlanOffsets o = plan_offsets(a.k, a.r, a.G);
+            a.off_idx = o.idx;
+            a.off_pos = o.pos;
+            a.off_irr_src = o.irr_src;
+        }
         RankPtrs codes = codes_in, scale = scale_in, zero = zero_in, outl = outl_in;
         a.T = a_in.T - row0 < rows_per_launch ? a_in.T - row0 : rows_per_launch;
         a.out = static_cast<uint8_t *>(a_in.out) + row0 * a_in.ldOut * ob;
@@ -272,9 +433,9 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
             if (zero.p[i]) zero.p[i] = static_cast<const uint8_t *>(zero.p[i]) + row0 * a_in.pitch_meta;
             if (outl.p[i]) outl.p[i] = static_cast<const uint8_t *>(outl.p[i]) + row0 * a_in.pitch_outl;
         }
-        const dim3 grid(static_cast<unsigned>(a.T), static_cast<unsigned>((tasks + 3) / 4));
-#define TPQ_LAUNCH3(LPG, ACC, OUT) \
-    k_decode_pass<LPG, ACC, OUT><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl)
+        const int rpw = rows_per_wave(a.step_c != nullptr, a.T, tasks);
+        const dim3 grid(static_cast<unsigned>((a.T + rpw - 1) / rpw), static_cast<unsigned>((tasks + 3) / 4));
+#define TPQ_LAUNCH3(LPG, ACC, OUT) launch_rows<LPG, ACC, OUT>(rpw, grid, s, a, codes, scale, zero, outl)
 #define TPQ_LAUNCH2(LPG)                                                                     \
     do {                                                                                     \
         if (accum == TPQ_ACC_FP32 && out_dtype == TPQ_OUT_BF16)                              \

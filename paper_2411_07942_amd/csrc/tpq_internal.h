@@ -233,7 +233,17 @@ struct DecodeArgs {
     // static symmetric mode: steps, fp32 [n_ranks][static_stride] in compacted order
     const float *step_c;
     int32_t static_stride;
+    // byte offsets of the plan's tables (what the header holds, known to the host too)
+    int32_t off_idx, off_pos, off_irr_src;
 };
+
+// What a kernel checks before it trusts a plan: one wide scalar load, no branches between
+// the fields.
+__device__ __forceinline__ bool plan_header_bad(const uint8_t *plan, int E, int k, int G)
+{
+    const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(plan);
+    return (ph->magic != kPlanMagic) | (ph->status != kPlanOk) | (ph->E != E) | (ph->k != k) | (ph->G != G);
+}
 
 // ---- host-side helpers --------------------------------------------------------
 
