@@ -8,12 +8,13 @@
 
 namespace tpq {
 
-// round a pair of floats to bf16 and return them as floats again
-__device__ __forceinline__ void round_pair_to_bf16(float &x, float &y)
+// A float rounded to bf16 (nearest even) and returned as a float again: the hardware's
+// pair conversion with a zero in the low half leaves exactly that in the register --
+// one instruction per value, against one and a half for converting pairs and taking
+// them apart again.
+__device__ __forceinline__ float round_via_bf16(float x)
 {
-    const uint32_t pk = pack_bf16x2(x, y);
-    x = bf16_lo_to_f32(pk);
-    y = bf16_hi_to_f32(pk);
+    return __uint_as_float(pack_bf16x2(0.0f, x));
 }
 
 // acc <- acc (+) x for 8 features at once, in the requested arithmetic
@@ -22,7 +23,7 @@ __device__ __forceinline__ void accumulate8(float (&acc)[8], float (&x)[8], bool
 {
     if (ACC == TPQ_ACC_BF16) {
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) round_pair_to_bf16(x[e], x[e + 1]);
+        for (int e = 0; e < 8; ++e) x[e] = round_via_bf16(x[e]);
     }
     if (first) {
 #pragma unroll
@@ -32,25 +33,107 @@ __device__ __forceinline__ void accumulate8(float (&acc)[8], float (&x)[8], bool
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] + x[e];
         if (ACC == TPQ_ACC_BF16) {
 #pragma unroll
-            for (int e = 0; e < 8; e += 2) round_pair_to_bf16(acc[e], acc[e + 1]);
+            for (int e = 0; e < 8; ++e) acc[e] = round_via_bf16(acc[e]);
         }
     }
 }
 
 // ---------------------------------------------------------------------------
+// Stores of one pass and row.  The wave parks its 512 sums in LDS in compacted order
+// (8 per lane), then lane s takes the pass's s-th store entry from the plan: a block of
+// 8 consecutive features that go to 8 consecutive columns -- read back from LDS at
+// whatever feature offset the block starts (two aligned 16-byte reads and a funnel
+// shift), written with one 128-bit store (two for fp32 output) -- or, for the few
+// features of runs shorter than 8, a single feature.  Selected columns cut the stream of
+// features into runs; blocks follow the runs, so no store is split feature by feature.
+// st: this wave's staging area (64 x 16 bytes for bf16 output, 128 x 16 for fp32).
+// e0, e1: the entries of slots lane and 64 + lane (loaded early); further entries are
+// read here.  All 64 lanes must call.
+// ---------------------------------------------------------------------------
+template <int OUT>
+__device__ __forceinline__ void store_pass(u32x4 *st, const float (&acc)[8], uint8_t *out_row,
+                                           uint32_t lane, const uint32_t *entries, uint32_t nb,
+                                           uint32_t nall, uint32_t e0, uint32_t e1)
+{
+    if (OUT == TPQ_OUT_FP32) {
+        st[2u * lane] = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]),
+                              __float_as_uint(acc[3])};
+        st[2u * lane + 1u] = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                   __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+    } else {
+        st[lane] = u32x4{pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                         pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7])};
+    }
+    wave_lds_fence();
+    for (uint32_t s0 = 0; s0 < nall; s0 += 64) {
+        const uint32_t slot = s0 + lane;
+        uint32_t e = s0 == 0 ? e0 : e1;
+        if (s0 >= 128) e = slot < nall ? entries[slot] : 0u;
+        const uint32_t col = e & 0xFFFFu, at = (e >> 16) & 0x1FFu;
+        if (slot < nb) {
+            if (OUT == TPQ_OUT_FP32) {
+                // 8 dwords from dword `at` on: three aligned reads, shift by at % 4 dwords
+                const uint32_t q = at >> 2;
+                const u32x4 A = st[q], B = st[min(q + 1u, 127u)], C = st[min(q + 2u, 127u)];
+                // (selects between named values: an indexed array here ends up in memory)
+                const bool s2 = (at & 2u) != 0, s1 = (at & 1u) != 0;
+#define TPQ_SEL(c, hi, lo) ((c) ? (hi) : (lo))
+                const uint32_t u0 = TPQ_SEL(s2, A.z, A.x), u1 = TPQ_SEL(s2, A.w, A.y), u2 = TPQ_SEL(s2, B.x, A.z),
+                               u3 = TPQ_SEL(s2, B.y, A.w), u4 = TPQ_SEL(s2, B.z, B.x), u5 = TPQ_SEL(s2, B.w, B.y),
+                               u6 = TPQ_SEL(s2, C.x, B.z), u7 = TPQ_SEL(s2, C.y, B.w), u8 = TPQ_SEL(s2, C.z, C.x);
+                const uint32_t o[8] = {TPQ_SEL(s1, u1, u0), TPQ_SEL(s1, u2, u1), TPQ_SEL(s1, u3, u2),
+                                       TPQ_SEL(s1, u4, u3), TPQ_SEL(s1, u5, u4), TPQ_SEL(s1, u6, u5),
+                                       TPQ_SEL(s1, u7, u6), TPQ_SEL(s1, u8, u7)};
+                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
+                                            reinterpret_cast<u32x4_a4 *>(out_row + 4u * col));
+                __builtin_nontemporal_store(u32x4{o[4], o[5], o[6], o[7]},
+                                            reinterpret_cast<u32x4_a4 *>(out_row + 4u * col + 16u));
+            } else {
+                // 8 half-words from half-word `at` on: two aligned reads, shift by at % 8
+                const uint32_t q = at >> 3;
+                const u32x4 A = st[q], B = st[min(q + 1u, 63u)];
+                const bool s2 = (at & 4u) != 0, s1 = (at & 2u) != 0;
+                const uint32_t sh = (at & 1u) << 4;
+                const uint32_t u0 = TPQ_SEL(s2, A.z, A.x), u1 = TPQ_SEL(s2, A.w, A.y), u2 = TPQ_SEL(s2, B.x, A.z),
+                               u3 = TPQ_SEL(s2, B.y, A.w), u4 = TPQ_SEL(s2, B.z, B.x), u5 = TPQ_SEL(s2, B.w, B.y);
+                const uint32_t v0 = TPQ_SEL(s1, u1, u0), v1 = TPQ_SEL(s1, u2, u1), v2 = TPQ_SEL(s1, u3, u2),
+                               v3 = TPQ_SEL(s1, u4, u3), v4 = TPQ_SEL(s1, u5, u4);
+#undef TPQ_SEL
+                const uint32_t o[4] = {__builtin_amdgcn_alignbit(v1, v0, sh), __builtin_amdgcn_alignbit(v2, v1, sh),
+                                       __builtin_amdgcn_alignbit(v3, v2, sh), __builtin_amdgcn_alignbit(v4, v3, sh)};
+                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
+                                            reinterpret_cast<u32x4_a2 *>(out_row + 2u * col));
+            }
+        } else if (slot < nall) {
+            const uint32_t *stw = reinterpret_cast<const uint32_t *>(st);
+            if (OUT == TPQ_OUT_FP32) {
+                *reinterpret_cast<uint32_t *>(out_row + 4u * col) = stw[at];
+            } else {
+                const uint32_t w = stw[at >> 1];
+                *reinterpret_cast<uint16_t *>(out_row + 2u * col) =
+                    static_cast<uint16_t>((at & 1u) ? (w >> 16) : (w & 0xFFFFu));
+            }
+        }
+    }
+    // A later call's staging writes follow these reads in program order, and a wave's LDS
+    // operations execute in order: nothing to wait for (a fence here would also hold the
+    // wave until its global stores have completed).
+    __builtin_amdgcn_wave_barrier();
+}
+
+// ---------------------------------------------------------------------------
 // One wavefront handles one pass (64 chunks = 512 compacted features) of one output
-// row, or up to 64 of the row's selected features; waves are independent (no LDS, no
-// barrier), so a CU always holds waves in every phase and loads, arithmetic and
-// stores overlap.
+// row, or up to 64 of the row's selected features; waves are independent (no barrier;
+// LDS only as each wave's private staging area for its stores), so a CU always holds
+// waves in every phase and loads, arithmetic and stores overlap.
 //
-// Pass wave: every lane issues all its loads at once -- the chunk's start column,
-// one 32-bit word of codes (8 features) per rank, the group's scale and zero per
-// rank -- then dequantises (code * scale + zero: one FMA, the product is exact) and
-// accumulates in ascending rank order.  The 8 sums are stored at the chunk's start
-// column with one 128-bit store (2-byte aligned: removing the selected columns
-// shifted the compacted stream; neighbouring lanes' stores are contiguous, so lines
-// are written whole).  A lane whose chunk an outlier splits stores its sums one by
-// one at the columns the plan lists.
+// Pass wave: every lane issues all its loads at once -- the pass's store entries, one
+// 32-bit word of codes (8 features) per rank, the group's scale and zero per rank --
+// then dequantises (code * scale + zero: one FMA, the product is exact) and
+// accumulates in ascending rank order.  The sums leave through store_pass(): blocks
+// of 8 consecutive columns, one 128-bit store each (2-byte aligned: removing the
+// selected columns shifted the compacted stream; neighbouring lanes' stores are
+// contiguous, so lines are written whole).
 // Outlier wave: lane p adds the ranks' bf16 values of outlier p and stores the sum at
 // its column.
 // grid: x = row, y = groups of 4 waves.
@@ -94,7 +177,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
                         acc = x;
                     } else {
                         acc = acc + x;
-                        if (ACC == TPQ_ACC_BF16) acc = bf16_lo_to_f32(pack_bf16x2(acc, acc));
+                        if (ACC == TPQ_ACC_BF16) acc = round_via_bf16(acc);
                     }
                 }
             }
@@ -107,15 +190,18 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     }
 
     // ---- one pass of quantised features ---------------------------------------------
-    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + a.off_pos);
-    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + a.off_irr_src);
     const uint32_t chunk = task * 64u + lane;
     const uint32_t g = min(chunk / LPG, ng - 1u);
+    // the pass's store entries: where they start, blocks, blocks + narrow entries
+    const uint4 sp = reinterpret_cast<const uint4 *>(a.plan + a.off_spass)[task];
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + sp.x;
+    const uint32_t nb = sp.y, nall = sp.y + sp.z;
+    const uint32_t e0 = lane < nall ? entries[lane] : 0u;
+    const uint32_t e1 = 64u + lane < nall ? entries[64u + lane] : 0u;
     // One 32-bit byte offset per section serves every rank (the host keeps
     // T * pitch below 2^31 per launch): the rank only changes the scalar base.
     const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
     const uint32_t off_meta = t * static_cast<uint32_t>(a.pitch_meta) + 2u * g;
-    const uint32_t cp = cpos[chunk];
     float acc[8];
 
     // 8 ranks at a time: all 24 loads first, then the arithmetic.  FULL batches index
@@ -157,45 +243,9 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     uint32_t i0 = 0;
     for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
     if (i0 < N) batch(i0, std::false_type{});
-    if (chunk >= chunks) return;
-
-    uint32_t o[8];  // the 8 results as output words (bf16: two per word)
-    if (OUT == TPQ_OUT_FP32) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = __float_as_uint(acc[e]);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
-    }
-    if (!(cp & kNotRegular)) {
-        const uint32_t col = cp & 0xFFFFu;
-        if (OUT == TPQ_OUT_FP32) {
-            __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
-                                        reinterpret_cast<u32x4_a4 *>(out_row + 4u * col));
-            __builtin_nontemporal_store(u32x4{o[4], o[5], o[6], o[7]},
-                                        reinterpret_cast<u32x4_a4 *>(out_row + 4u * col + 16u));
-        } else {
-            __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
-                                        reinterpret_cast<u32x4_a2 *>(out_row + 2u * col));
-        }
-    } else {
-        // split (or ragged last) chunk: one store per feature
-        const uint32_t slot = (cp >> 16) & 0x7FFFu;
-        const u32x4 tab = *reinterpret_cast<const u32x4 *>(irr_src + 8u * slot);
-        const uint32_t col[8] = {tab.x & 0xFFFFu, tab.x >> 16, tab.y & 0xFFFFu, tab.y >> 16,
-                                 tab.z & 0xFFFFu, tab.z >> 16, tab.w & 0xFFFFu, tab.w >> 16};
-        const int n_valid = a.r - 8 * static_cast<int>(chunk);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (e < n_valid) {
-                if (OUT == TPQ_OUT_FP32)
-                    *reinterpret_cast<uint32_t *>(out_row + 4u * col[e]) = o[e];
-                else
-                    *reinterpret_cast<uint16_t *>(out_row + 2u * col[e]) =
-                        static_cast<uint16_t>((e & 1) ? (o[e >> 1] >> 16) : (o[e >> 1] & 0xFFFFu));
-            }
-        }
-    }
+    __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
+    store_pass<OUT>(stage + wave * (64u * (OUT == TPQ_OUT_FP32 ? 2u : 1u)), acc, out_row, lane, entries, nb,
+                    nall, e0, e1);
 }
 
 // ---------------------------------------------------------------------------
@@ -258,7 +308,7 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
                             acc[rr] = x;
                         } else {
                             acc[rr] = acc[rr] + x;
-                            if (ACC == TPQ_ACC_BF16) acc[rr] = bf16_lo_to_f32(pack_bf16x2(acc[rr], acc[rr]));
+                            if (ACC == TPQ_ACC_BF16) acc[rr] = round_via_bf16(acc[rr]);
                         }
                     }
                 }
@@ -277,19 +327,19 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     }
 
     // ---- one pass of quantised features ---------------------------------------------
-    const uint32_t *cpos = reinterpret_cast<const uint32_t *>(a.plan + a.off_pos);
-    const uint16_t *irr_src = reinterpret_cast<const uint16_t *>(a.plan + a.off_irr_src);
     const uint32_t chunk = task * 64u + lane;
+    // the pass's store entries: where they start, blocks, blocks + narrow entries
+    const uint4 sp = reinterpret_cast<const uint4 *>(a.plan + a.off_spass)[task];
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + sp.x;
+    const uint32_t nb = sp.y, nall = sp.y + sp.z;
+    const uint32_t e0 = lane < nall ? entries[lane] : 0u;
+    const uint32_t e1 = 64u + lane < nall ? entries[64u + lane] : 0u;
     // One 32-bit byte offset per section and row serves every rank (the host keeps
     // T * pitch below 2^31 per launch): the rank only changes the scalar base.
     uint32_t off_codes[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr)
         off_codes[rr] = tr[rr] * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
-    const uint32_t cp = cpos[chunk];
-    // a split chunk's 8 columns: fetched now, so that the load overlaps the others
-    u32x4 tab = {0u, 0u, 0u, 0u};
-    if (cp & kNotRegular) tab = *reinterpret_cast<const u32x4 *>(irr_src + 8u * ((cp >> 16) & 0x7FFFu));
     float acc[R][8];
 
     // static mode, 4 ranks at a time: a code word per row and 8 steps each
@@ -332,46 +382,12 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     uint32_t i0 = 0;
     for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
     if (i0 < N) batch_static(i0, std::false_type{});
-    if (chunk >= chunks) return;
-
+    __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         if (static_cast<uint32_t>(rr) >= n_rows) break;  // uniform
-        uint32_t o[8];  // the 8 results as output words (bf16: two per word)
-        if (OUT == TPQ_OUT_FP32) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = __float_as_uint(acc[rr][e]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[rr][2 * e], acc[rr][2 * e + 1]);
-        }
-        if (!(cp & kNotRegular)) {
-            const uint32_t col = cp & 0xFFFFu;
-            if (OUT == TPQ_OUT_FP32) {
-                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
-                                            reinterpret_cast<u32x4_a4 *>(out_row[rr] + 4u * col));
-                __builtin_nontemporal_store(u32x4{o[4], o[5], o[6], o[7]},
-                                            reinterpret_cast<u32x4_a4 *>(out_row[rr] + 4u * col + 16u));
-            } else {
-                __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]},
-                                            reinterpret_cast<u32x4_a2 *>(out_row[rr] + 2u * col));
-            }
-        } else {
-            // split (or ragged last) chunk: one store per feature
-            const uint32_t col[8] = {tab.x & 0xFFFFu, tab.x >> 16, tab.y & 0xFFFFu, tab.y >> 16,
-                                     tab.z & 0xFFFFu, tab.z >> 16, tab.w & 0xFFFFu, tab.w >> 16};
-            const int n_valid = a.r - 8 * static_cast<int>(chunk);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if (e < n_valid) {
-                    if (OUT == TPQ_OUT_FP32)
-                        *reinterpret_cast<uint32_t *>(out_row[rr] + 4u * col[e]) = o[e];
-                    else
-                        *reinterpret_cast<uint16_t *>(out_row[rr] + 2u * col[e]) =
-                            static_cast<uint16_t>((e & 1) ? (o[e >> 1] >> 16) : (o[e >> 1] & 0xFFFFu));
-                }
-            }
-        }
+        store_pass<OUT>(stage + wave * (64u * (OUT == TPQ_OUT_FP32 ? 2u : 1u)), acc[rr], out_row[rr], lane,
+                        entries, nb, nall, e0, e1);
     }
 }
 
@@ -421,8 +437,8 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
         {
             const PlanOffsets o = plan_offsets(a.k, a.r, a.G);
             a.off_idx = o.idx;
-            a.off_pos = o.pos;
-            a.off_irr_src = o.irr_src;
+            a.off_spass = o.spass;
+            a.off_sblk = o.sblk;
         }
         RankPtrs codes = codes_in, scale = scale_in, zero = zero_in, outl = outl_in;
         a.T = a_in.T - row0 < rows_per_launch ? a_in.T - row0 : rows_per_launch;

@@ -84,6 +84,18 @@ namespace tpq {
 //                                       (feature e at bits 4e..4e+3) in the slot's 32 bytes,
 //                                       word 1 = byte offset of its second window in the
 //                                       row | kDirWide8 for a "wide" slot (see dirr)
+//
+// Tables of the decoder's stores.  The 512 sums of a pass (in compacted order) go to
+// runs of consecutive output columns; selected columns and the pass's ends cut the
+// runs.  A run of 8 or more features is covered by "blocks" of 8 consecutive features
+// = 8 consecutive columns (the last block of a run is aligned to the run's end and may
+// repeat features of the block before it); the features of shorter runs are stored
+// one by one ("narrow" entries).
+//   spass    uint32[4 * passes]         per pass: first entry in sblk, blocks, narrow
+//                                       entries, 0
+//   sblk     uint32[sblk_cap_of()]      per pass its blocks, then its narrow entries:
+//                                       bits 15..0 = first column, bits 24..16 = first
+//                                       feature's position within the pass (0..511)
 constexpr uint32_t kPlanMagic = 0x51505434u;  // "4TPQ"
 constexpr int kPlanOk = 1;
 constexpr int kPlanBadIndex = 2;
@@ -126,7 +138,10 @@ struct PlanHeader {
     int32_t dseg_offset;
     int32_t drec_offset;
     int32_t drec2_offset;
-    int32_t reserved[4];
+    int32_t spass_offset;
+    int32_t sblk_offset;
+    int32_t sblk_cap;     // entries sblk has room for
+    int32_t reserved[1];
 };
 static_assert(sizeof(PlanHeader) == 128, "plan header is 128 bytes");
 
@@ -166,11 +181,20 @@ __host__ __device__ inline int dir_segs_of(int passes)
     return passes > 0 ? (passes + P - 1) / P : 0;
 }
 
+// Entries of sblk: a block per chunk, one more per run (at most one run per selected
+// feature and pass), up to 7 narrow entries per run -- and never more than 9 per chunk.
+__host__ __device__ inline int sblk_cap_of(int k, int r)
+{
+    const int cp = chunks_padded_of(r);
+    const int bound = cp + 8 * (k + cp / 64);
+    return bound < 9 * cp ? bound : 9 * cp;
+}
+
 __host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
 
 struct PlanOffsets {
     int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src;
-    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, drec2, total;
+    int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, drec2, spass, sblk, total;
 };
 __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
 {
@@ -194,7 +218,9 @@ __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
     o.dseg = o.dslot8 + (8 * dir_slots_of(k, r) + 15) / 16 * 16;
     o.drec = o.dseg + (8 * dir_segs_of(cp / 64) + 15) / 16 * 16;
     o.drec2 = o.drec + dir_segs_of(cp / 64) * 64 * 32;
-    o.total = o.drec2 + dir_segs_of(cp / 64) * 64 * 16;
+    o.spass = o.drec2 + dir_segs_of(cp / 64) * 64 * 16;
+    o.sblk = o.spass + (cp / 64) * 16;
+    o.total = o.sblk + (4 * sblk_cap_of(k, r) + 15) / 16 * 16;
     return o;
 }
 
@@ -234,7 +260,7 @@ struct DecodeArgs {
     const float *step_c;
     int32_t static_stride;
     // byte offsets of the plan's tables (what the header holds, known to the host too)
-    int32_t off_idx, off_pos, off_irr_src;
+    int32_t off_idx, off_spass, off_sblk;
 };
 
 // What a kernel checks before it trusts a plan: one wide scalar load, no branches between

@@ -40,7 +40,10 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->dseg_offset = o.dseg;
         h->drec_offset = o.drec;
         h->drec2_offset = o.drec2;
-        for (int i = 0; i < 4; ++i) h->reserved[i] = 0;
+        h->spass_offset = o.spass;
+        h->sblk_offset = o.sblk;
+        h->sblk_cap = sblk_cap_of(k, r);
+        h->reserved[0] = 0;
     }
 }
 
@@ -344,6 +347,75 @@ __global__ void k_plan_drec(uint8_t *plan, int chunks_padded, PlanOffsets o)
     rec2[3] = 0u;
 }
 
+// Store blocks of the decoder, one workgroup of 512 threads per pass, thread = feature.
+// FILL = false: count the pass's blocks and narrow entries into spass; FILL = true
+// (after k_plan_sblk_offsets): write the entries.
+template <bool FILL>
+__global__ __launch_bounds__(512) void k_plan_sblk(uint8_t *plan, int r, PlanOffsets o, int cap)
+{
+    __shared__ uint8_t start[512], kind[512];
+    PlanHeader *h = reinterpret_cast<PlanHeader *>(plan);
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
+    uint32_t *spass = reinterpret_cast<uint32_t *>(plan + o.spass);
+    uint32_t *sblk = reinterpret_cast<uint32_t *>(plan + o.sblk);
+    const int p = blockIdx.x, a0 = threadIdx.x;
+    const int c = 512 * p + a0;
+    const int n = min(512, r - 512 * p);  // features of this pass
+    const bool real = a0 < n;
+    start[a0] = real && (a0 == 0 || src[c] != src[c - 1] + 1);
+    __syncthreads();
+    int rs = a0, re = a0 + 1;  // the run [rs, re) that holds this feature
+    if (real) {
+        while (!start[rs]) --rs;
+        while (re < n && !start[re]) ++re;
+    }
+    const int len = re - rs;
+    // 1: leads a block; 2: narrow
+    kind[a0] = !real ? 0 : (len < 8 ? 2 : ((a0 - rs) % 8 == 0 ? 1 : 0));
+    __syncthreads();
+    int before1 = 0, before2 = 0, n1 = 0, n2 = 0;
+    for (int i = 0; i < 512; ++i) {
+        const int kd = kind[i];
+        n1 += kd == 1;
+        n2 += kd == 2;
+        if (i < a0) {
+            before1 += kd == 1;
+            before2 += kd == 2;
+        }
+    }
+    if (!FILL) {
+        if (a0 == 0) {
+            spass[4 * p + 1] = n1;
+            spass[4 * p + 2] = n2;
+            spass[4 * p + 3] = 0;
+        }
+        return;
+    }
+    const int first = spass[4 * p];
+    if (first + n1 + n2 > cap) {
+        if (a0 == 0) h->status = kPlanInternal;
+        return;
+    }
+    if (kind[a0] == 1) {
+        const int a = a0 + 8 <= re ? a0 : re - 8;
+        sblk[first + before1] = src[512 * p + a] | (static_cast<uint32_t>(a) << 16);
+    } else if (kind[a0] == 2) {
+        sblk[first + n1 + before2] = src[c] | (static_cast<uint32_t>(a0) << 16);
+    }
+}
+
+__global__ void k_plan_sblk_offsets(uint8_t *plan, int passes, PlanOffsets o)
+{
+    uint32_t *spass = reinterpret_cast<uint32_t *>(plan + o.spass);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        uint32_t at = 0;
+        for (int p = 0; p < passes; ++p) {
+            spass[4 * p] = at;
+            at += spass[4 * p + 1] + spass[4 * p + 2];
+        }
+    }
+}
+
 // Static symmetric mode (Sec. 3): per device i and compacted position c (feature j =
 // src_of[c]): R = 2*max(-m, M), step = R/15, inv = 1/step; a vanishing range gives 0, 0.
 __global__ void k_static_params(const uint8_t *plan, const float *__restrict__ m,
@@ -398,6 +470,11 @@ int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipSt
     if (cp > 0) k_plan_dseg<<<1, 64, 0, s>>>(p, k, cp, o);
     if (k > 0) k_plan_dsel<<<((k + 3) / 4 * 4 + 255) / 256, 256, 0, s>>>(p, E, k, r, o);
     if (cp > 0) k_plan_drec<<<(dir_segs_of(cp / 64) * 64 + 255) / 256, 256, 0, s>>>(p, cp, o);
+    if (cp > 0) {
+        k_plan_sblk<false><<<cp / 64, 512, 0, s>>>(p, r, o, sblk_cap_of(k, r));
+        k_plan_sblk_offsets<<<1, 64, 0, s>>>(p, cp / 64, o);
+        k_plan_sblk<true><<<cp / 64, 512, 0, s>>>(p, r, o, sblk_cap_of(k, r));
+    }
     return hip_result(hipGetLastError());
 }
 

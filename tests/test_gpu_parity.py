@@ -183,6 +183,46 @@ def test_plan_tables_and_bad_indices():
         tpq.plan_check(L2, plan)
 
 
+@pytest.mark.parametrize("E,cols", [
+    (2048, [3, 100, 101, 102, 700, 705, 1029, 2047]),
+    (1032, [0]),
+    (520, list(range(1, 520, 9))),                 # every run is 8 features long
+    (1024, list(range(4, 1024, 7))),               # every run is shorter than 8: narrow entries only
+    (4096, []),
+])
+def test_plan_store_blocks(E, cols):
+    """The decoder's store table against its definition: per pass of 512 compacted features,
+    runs of consecutive columns; a run of 8 or more is covered by blocks of 8 (the last one
+    aligned to the run's end), shorter runs feature by feature."""
+    idx = np.array(cols, np.int32)
+    k = idx.size
+    L = tpq.layout_init(E, k, 128)
+    raw = gpu_plan(L, idx).cpu().numpy()
+    hdr = raw[:128].view(np.int32)
+    spass_off, sblk_off, cap = hdr[28], hdr[29], hdr[30]
+    src = compaction(idx, E)
+    r = E - k
+    passes = (r + 511) // 512
+    spass = raw[spass_off: spass_off + 16 * passes].view(np.uint32).reshape(passes, 4)
+    sblk = raw[sblk_off: sblk_off + 4 * cap].view(np.uint32)
+    at = 0
+    for p in range(passes):
+        feats = src[512 * p: min(512 * (p + 1), r)]
+        cuts = [0] + [i for i in range(1, feats.size) if feats[i] != feats[i - 1] + 1] + [feats.size]
+        blocks, narrow = [], []
+        for rs, re in zip(cuts[:-1], cuts[1:]):
+            if re - rs >= 8:
+                for a0 in range(rs, re, 8):
+                    a = a0 if a0 + 8 <= re else re - 8
+                    blocks.append(int(feats[a]) | (a << 16))
+            else:
+                narrow += [int(feats[a]) | (a << 16) for a in range(rs, re)]
+        assert list(spass[p]) == [at, len(blocks), len(narrow), 0]
+        assert list(sblk[at: at + len(blocks) + len(narrow)]) == blocks + narrow
+        at += len(blocks) + len(narrow)
+    assert at <= cap
+
+
 def test_determinism():
     w = dataclasses.replace(wl.LLAMA_PREFILL, T=64)
     Ys = wl.partial_sums(w, device="cuda")
