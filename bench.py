@@ -26,17 +26,18 @@ import torch
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak bandwidth
 # HBM bytes per tpq_encode launch on this workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 179.4 MB read
-# + 50.0 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
-ENCODE_TRAFFIC_BYTES = 229_460_000
-DECODE_TRAFFIC_BYTES = 83_890_000
+# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 186.0 MB read
+# + 49.9 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
+ENCODE_TRAFFIC_BYTES = 235_820_000
+DECODE_TRAFFIC_BYTES = 84_570_000
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500,
+                    help="untimed steps first (the GPU needs some tens of ms of load to reach steady clocks)")
     ap.add_argument("--sets", type=int, default=6, help="independent buffer sets rotated per step")
     ap.add_argument("--accum", choices=["bf16", "fp32"], default="bf16",
                     help="arithmetic of the sum over ranks in tpq_decode_reduce (the other mode is "
