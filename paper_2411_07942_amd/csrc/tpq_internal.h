@@ -20,23 +20,6 @@ namespace tpq {
 //   src_of   uint16[chunks_padded * 8]  src_of[c] = feature index of compacted
 //                                       position c; positions >= r repeat the
 //                                       last real one (harmless for min / max)
-//   cpos     uint32[chunks_padded]      per chunk: bits 15..0 = a column from which
-//                                       16 bytes can always be read; for a "regular"
-//                                       chunk (its 8 features are consecutive
-//                                       columns) that is the chunk's first column
-//                                       and the whole word is just that.  Bit 31 set:
-//                                       an outlier splits the chunk or it is the
-//                                       ragged last one ("irregular"; bits 30..16 =
-//                                       its slot q in irr / irr_src), or the chunk
-//                                       lies beyond the row: if it shares the last
-//                                       real group it has a slot too (its 8 sources
-//                                       repeat the last feature, neutral for the
-//                                       group's min / max), else slot = kNoSlot.
-//   flags    uint16[chunks_padded]      scratch of the build (1 = irregular)
-//   irr      uint16[chunks_padded]      irr[q] = chunk number of the q-th irregular
-//                                       chunk, ascending
-//   pass_irr uint16[passes + 1]         irregular chunks below pass p
-//   irr_src  uint16[8 * slots]          the 8 feature indices of irregular chunk q
 //   pass_col uint16[passes + 1]         column of the first feature of pass p
 //                                       (pass_col[passes] = E)
 //
@@ -100,8 +83,6 @@ constexpr uint32_t kPlanMagic = 0x51505434u;  // "4TPQ"
 constexpr int kPlanOk = 1;
 constexpr int kPlanBadIndex = 2;
 constexpr int kPlanInternal = 3;  // a table of the build overflowed (never expected)
-constexpr uint32_t kNotRegular = 0x80000000u;
-constexpr uint32_t kNoSlot = 0x7FFFu;
 // beyond the row: flag + no slot; the low bits then hold column E - 8
 constexpr uint32_t kDirOdd = 0x8000u;
 constexpr uint32_t kDirAbsent = 0x40000000u;
@@ -120,12 +101,7 @@ struct PlanHeader {
     int32_t chunks_padded;  // chunks rounded up to a multiple of 64
     int32_t idx_offset;     // byte offsets from the start of the plan
     int32_t src_offset;
-    int32_t pos_offset;
     int32_t pass_col_offset;
-    int32_t irr_offset;
-    int32_t pass_irr_offset;
-    int32_t n_irr;
-    int32_t irr_src_offset;
     int32_t dpos_offset;
     int32_t dirr_offset;
     int32_t dsel_offset;
@@ -141,7 +117,7 @@ struct PlanHeader {
     int32_t spass_offset;
     int32_t sblk_offset;
     int32_t sblk_cap;     // entries sblk has room for
-    int32_t reserved[1];
+    int32_t reserved[6];
 };
 static_assert(sizeof(PlanHeader) == 128, "plan header is 128 bytes");
 
@@ -149,16 +125,7 @@ __host__ __device__ inline int chunks_of(int r) { return (r + 7) / 8; }
 __host__ __device__ inline int chunks_padded_of(int r) { return (chunks_of(r) + 63) / 64 * 64; }
 __host__ __device__ inline int idx_bytes_of(int k) { return ((k + 3) / 4 * 4) * 4; }
 
-// an upper bound of the irregular chunks of a row that the host can compute
-__host__ __device__ inline int irr_slots_of(int k, int r, int G)
-{
-    // chunks split by an outlier or ragged (at most k + 1, and no more than there are
-    // chunks), plus the absent chunks that share the last real group (fewer than G / 8)
-    const int c = chunks_of(r);
-    return (k + 1 < c ? k + 1 : c) + G / 8 - 1;
-}
-
-// ... and of the chunks that need a slot in the encoder's tables: one per selected
+// An upper bound of the chunks that need a slot in the encoder's tables: one per selected
 // feature at most (the chunk that holds or precedes it), the ragged last chunk, the
 // last chunk of every pass, and the chunks next to the row's end
 __host__ __device__ inline int dir_slots_of(int k, int r)
@@ -193,7 +160,7 @@ __host__ __device__ inline int sblk_cap_of(int k, int r)
 __host__ __device__ inline int pass_tab_bytes_of(int r) { return ((chunks_padded_of(r) / 64 + 1) * 2 + 15) / 16 * 16; }
 
 struct PlanOffsets {
-    int idx, src, pos, flags, irr, pass_irr, pass_col, irr_src;
+    int idx, src, pass_col;
     int dpos, dflags, dirr, dsel, pass_dirr, dpos16, dslot8, dseg, drec, drec2, spass, sblk, total;
 };
 __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
@@ -202,13 +169,8 @@ __host__ __device__ inline PlanOffsets plan_offsets(int k, int r, int G)
     PlanOffsets o;
     o.idx = sizeof(PlanHeader);
     o.src = o.idx + idx_bytes_of(k);
-    o.pos = o.src + 16 * cp;
-    o.flags = o.pos + 4 * cp;
-    o.irr = o.flags + 2 * cp;
-    o.pass_irr = o.irr + 2 * cp;
-    o.pass_col = o.pass_irr + pass_tab_bytes_of(r);
-    o.irr_src = o.pass_col + pass_tab_bytes_of(r);
-    o.dpos = o.irr_src + 16 * irr_slots_of(k, r, G);
+    o.pass_col = o.src + 16 * cp;
+    o.dpos = o.pass_col + pass_tab_bytes_of(r);
     o.dflags = o.dpos + 4 * cp;
     o.dirr = o.dflags + (2 * cp + 15) / 16 * 16;
     o.dsel = o.dirr + 16 * dir_slots_of(k, r);

@@ -22,12 +22,7 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->chunks_padded = chunks_padded;
         h->idx_offset = o.idx;
         h->src_offset = o.src;
-        h->pos_offset = o.pos;
         h->pass_col_offset = o.pass_col;
-        h->irr_offset = o.irr;
-        h->pass_irr_offset = o.pass_irr;
-        h->n_irr = 0;
-        h->irr_src_offset = o.irr_src;
         h->dpos_offset = o.dpos;
         h->dirr_offset = o.dirr;
         h->dsel_offset = o.dsel;
@@ -43,7 +38,7 @@ __global__ void k_plan_init(uint8_t *plan, int E, int k, int G, int r, int chunk
         h->spass_offset = o.spass;
         h->sblk_offset = o.sblk;
         h->sblk_cap = sblk_cap_of(k, r);
-        h->reserved[0] = 0;
+        for (int i = 0; i < 6; ++i) h->reserved[i] = 0;
     }
 }
 
@@ -89,69 +84,14 @@ __global__ void k_plan_pad(uint8_t *plan, int r, int chunks_padded, PlanOffsets 
     if (r > 0 && c < 8 * chunks_padded) src[c] = src[r - 1];
 }
 
-// flags[c] = 1 if chunk c cannot be served by one 16-byte access: an outlier sits
-// between its first and last feature, or it is the ragged last chunk.
-__global__ void k_plan_flags(uint8_t *plan, int r, int chunks, int chunks_padded, int lpg,
-                             PlanOffsets o)
+// pass_col[p] = column of the first feature of pass p; pass_col[passes] = E
+__global__ void k_plan_pass_col(uint8_t *plan, int E, int chunks, int passes, PlanOffsets o)
 {
-    const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
     const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
-    uint16_t *flags = reinterpret_cast<uint16_t *>(plan + o.flags);
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= chunks_padded) return;
-    uint16_t f = 0;
-    if (h->status == kPlanOk && chunks > 0) {
-        if (c < chunks) {
-            const bool ragged = 8 * c + 8 > r;
-            f = (ragged || src[8 * c + 7] - src[8 * c] != 7) ? 1 : 0;
-        } else {
-            // beyond the row but inside the last real group: gets a slot whose sources
-            // all repeat the last feature
-            f = (c / lpg == (chunks - 1) / lpg) ? 1 : 0;
-        }
-    }
-    flags[c] = f;
-}
-
-// cpos / irr / irr_src / pass_irr from the flags: the slot of an irregular chunk is
-// the number of irregular chunks before it.
-__global__ void k_plan_slots(uint8_t *plan, int E, int chunks, int chunks_padded, int slots,
-                             PlanOffsets o)
-{
-    PlanHeader *h = reinterpret_cast<PlanHeader *>(plan);
-    const uint16_t *src = reinterpret_cast<const uint16_t *>(plan + o.src);
-    const uint16_t *flags = reinterpret_cast<const uint16_t *>(plan + o.flags);
-    uint32_t *cpos = reinterpret_cast<uint32_t *>(plan + o.pos);
-    uint16_t *irr = reinterpret_cast<uint16_t *>(plan + o.irr);
-    uint16_t *pass_irr = reinterpret_cast<uint16_t *>(plan + o.pass_irr);
-    uint16_t *irr_src = reinterpret_cast<uint16_t *>(plan + o.irr_src);
     uint16_t *pass_col = reinterpret_cast<uint16_t *>(plan + o.pass_col);
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c > chunks_padded) return;
-    int q = 0;
-    for (int b = 0; b < c; ++b) q += flags[b];
-    if (c == chunks_padded) {  // one extra thread: the totals
-        h->n_irr = q;
-        pass_irr[chunks_padded / 64] = static_cast<uint16_t>(q);
-        pass_col[chunks_padded / 64] = static_cast<uint16_t>(E);
-        return;
-    }
-    if ((c & 63) == 0) {
-        pass_irr[c / 64] = static_cast<uint16_t>(q);
-        pass_col[c / 64] = c < chunks ? src[8 * c] : static_cast<uint16_t>(E);
-    }
-    if (h->status != kPlanOk || (c >= chunks && !flags[c])) {
-        cpos[c] = kNotRegular | (kNoSlot << 16) | static_cast<uint32_t>(E - 8);
-    } else if (flags[c] && q < slots) {
-        int safe = src[8 * c];
-        if (safe > E - 8) safe = E - 8;  // a 16-byte read from here stays inside the row
-        cpos[c] = kNotRegular | (static_cast<uint32_t>(q) << 16) | static_cast<uint32_t>(safe);
-        irr[q] = static_cast<uint16_t>(c);
-        for (int e = 0; e < 8; ++e) irr_src[8 * q + e] = src[8 * c + e];
-    } else {
-        cpos[c] = c < chunks ? src[8 * c]
-                             : (kNotRegular | (kNoSlot << 16) | static_cast<uint32_t>(E - 8));
-    }
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > passes) return;
+    pass_col[p] = (p < passes && 64 * p < chunks) ? src[512 * p] : static_cast<uint16_t>(E);
 }
 
 // ---- tables of the encoder that loads each chunk straight from the row -------------
@@ -463,8 +403,7 @@ int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipSt
     k_plan_build<<<(E + 255) / 256, 256, 0, s>>>(p, idx, E, k, r, o);
     const int tail = 8 * cp - r;
     if (r > 0 && tail > 0) k_plan_pad<<<(tail + 255) / 256, 256, 0, s>>>(p, r, cp, o);
-    if (cp > 0) k_plan_flags<<<(cp + 255) / 256, 256, 0, s>>>(p, r, chunks, cp, L->G / 8, o);
-    k_plan_slots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, chunks, cp, irr_slots_of(k, r, L->G), o);
+    k_plan_pass_col<<<1, 128, 0, s>>>(p, E, chunks, cp / 64, o);
     if (cp > 0) k_plan_dflags<<<(cp + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, o);
     k_plan_dslots<<<(cp + 1 + 255) / 256, 256, 0, s>>>(p, E, r, chunks, cp, dir_slots_of(k, r), o);
     if (cp > 0) k_plan_dseg<<<1, 64, 0, s>>>(p, k, cp, o);

@@ -199,7 +199,7 @@ def test_plan_store_blocks(E, cols):
     L = tpq.layout_init(E, k, 128)
     raw = gpu_plan(L, idx).cpu().numpy()
     hdr = raw[:128].view(np.int32)
-    spass_off, sblk_off, cap = hdr[28], hdr[29], hdr[30]
+    spass_off, sblk_off, cap = hdr[23], hdr[24], hdr[25]
     src = compaction(idx, E)
     r = E - k
     passes = (r + 511) // 512
