@@ -56,6 +56,9 @@ def _load():
         lib.orc_encode.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp,
                                           i32, i32, vp, i32]
+        lib.orc_encode_bits.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+        lib.orc_decode_reduce_bits.argtypes = [i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                               i32, i32, vp, i32]
         lib.orc_static_params.argtypes = [vp, vp, i32, i32, vp, vp]
         lib.orc_encode_static.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce_static.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp, i32, i32,
@@ -118,34 +121,56 @@ class Message:
     zero: np.ndarray   # uint16 [T,ng]  bf16 group minimum
 
 
-def dims(E: int, k: int, G: int):
+def dims(E: int, k: int, G: int, bits: int = 4):
     r = E - k
-    return r, (r + 1) // 2, (r + G - 1) // G
+    return r, (r * bits + 7) // 8, (r + G - 1) // G
 
 
-def encode(Y, idx_sorted, G: int, threads: int = 1) -> Message:
+def encode(Y, idx_sorted, G: int, threads: int = 1, bits: int = 4) -> Message:
+    """bits = 4: the primary path; other widths (Sec. 4, Fig. 3) go through the generic routine."""
     Y = _u16(Y)
     T, E = Y.shape
     idx_sorted = np.ascontiguousarray(idx_sorted, dtype=np.int32)
     k = idx_sorted.shape[0]
-    r, cb, ng = dims(E, k, G)
+    r, cb, ng = dims(E, k, G, bits)
     msg = Message(np.empty((T, k), np.uint16), np.empty((T, cb), np.uint8),
                   np.empty((T, ng), np.uint16), np.empty((T, ng), np.uint16))
-    rc = _load().orc_encode(_ptr(Y), T, E, E, k, G, _ptr(idx_sorted), _ptr(msg.outl),
-                            _ptr(msg.codes), _ptr(msg.scale), _ptr(msg.zero), threads)
+    if bits == 4:
+        rc = _load().orc_encode(_ptr(Y), T, E, E, k, G, _ptr(idx_sorted), _ptr(msg.outl),
+                                _ptr(msg.codes), _ptr(msg.scale), _ptr(msg.zero), threads)
+    else:
+        rc = _load().orc_encode_bits(_ptr(Y), T, E, E, k, G, bits, _ptr(idx_sorted), _ptr(msg.outl),
+                                     _ptr(msg.codes), _ptr(msg.scale), _ptr(msg.zero), threads)
     if rc:
         raise ValueError("orc_encode: bad arguments")
     return msg
 
 
+def encode_bits(Y, idx_sorted, G: int, bits: int, threads: int = 1) -> Message:
+    """Always the generic routine (also for bits = 4: the cross-check of the two)."""
+    Y = _u16(Y)
+    T, E = Y.shape
+    idx_sorted = np.ascontiguousarray(idx_sorted, dtype=np.int32)
+    k = idx_sorted.shape[0]
+    r, cb, ng = dims(E, k, G, bits)
+    msg = Message(np.empty((T, k), np.uint16), np.empty((T, cb), np.uint8),
+                  np.empty((T, ng), np.uint16), np.empty((T, ng), np.uint16))
+    rc = _load().orc_encode_bits(_ptr(Y), T, E, E, k, G, bits, _ptr(idx_sorted), _ptr(msg.outl),
+                                 _ptr(msg.codes), _ptr(msg.scale), _ptr(msg.zero), threads)
+    if rc:
+        raise ValueError("orc_encode_bits: bad arguments")
+    return msg
+
+
 def decode_reduce(msgs, idx_sorted, E: int, G: int, accum: int = ACC_FP32,
-                  out_fp32: bool = False, threads: int = 1) -> np.ndarray:
+                  out_fp32: bool = False, threads: int = 1, bits: int = 4,
+                  generic: bool = False) -> np.ndarray:
     """Dequantise the N messages and add them in ascending device order."""
     N = len(msgs)
     idx_sorted = np.ascontiguousarray(idx_sorted, dtype=np.int32)
     k = idx_sorted.shape[0]
     T = msgs[0].codes.shape[0] if k < E else msgs[0].outl.shape[0]
-    r, cb, ng = dims(E, k, G)
+    r, cb, ng = dims(E, k, G, bits)
     keep = []
 
     def table(name, dtype, shape):
@@ -162,16 +187,20 @@ def decode_reduce(msgs, idx_sorted, E: int, G: int, accum: int = ACC_FP32,
     zero = table("zero", np.uint16, (T, ng))
     outl = table("outl", np.uint16, (T, k))
     out = np.empty((T, E), np.float32 if out_fp32 else np.uint16)
-    rc = _load().orc_decode_reduce(N, T, E, k, G, _ptr(idx_sorted), codes, scale, zero, outl,
-                                   accum, int(bool(out_fp32)), _ptr(out), threads)
+    if bits == 4 and not generic:
+        rc = _load().orc_decode_reduce(N, T, E, k, G, _ptr(idx_sorted), codes, scale, zero, outl,
+                                       accum, int(bool(out_fp32)), _ptr(out), threads)
+    else:
+        rc = _load().orc_decode_reduce_bits(N, T, E, k, G, bits, _ptr(idx_sorted), codes, scale, zero,
+                                            outl, accum, int(bool(out_fp32)), _ptr(out), threads)
     if rc:
         raise ValueError("orc_decode_reduce: bad arguments")
     return out
 
 
-def dequantize(msg: Message, idx_sorted, E: int, G: int) -> np.ndarray:
+def dequantize(msg: Message, idx_sorted, E: int, G: int, bits: int = 4) -> np.ndarray:
     """x_hat fp32 [T,E] of one message (the N = 1, fp32 case of decode_reduce)."""
-    return decode_reduce([msg], idx_sorted, E, G, ACC_FP32, out_fp32=True)
+    return decode_reduce([msg], idx_sorted, E, G, ACC_FP32, out_fp32=True, bits=bits)
 
 
 # ---- static symmetric mode (the paper's own quantiser, Sec. 3) ---------------------

@@ -46,6 +46,14 @@
  *   whose calibrated range vanishes (step < 1e-30) is sent as code 0 and
  *   comes back as 0.  Nothing but codes and the BF16 features travels.
  *
+ *   other bit widths (paper Sec. 4, the experiment that varies the number of
+ *   bits of the quantised features, Fig. 3): the same dynamic group-wise
+ *   quantiser with b in {2, 3, 4, 5, 6, 8} bits: 2^b - 1 steps over the group's
+ *   range, scale = bf16((max-min)/(2^b - 1)), codes 0..2^b - 1.  The codes of a
+ *   row form one little-endian bit string: code c occupies bits b*c .. b*c+b-1,
+ *   bit n of the string being bit n%8 of byte n/8 (for b = 4 this is "two codes
+ *   per byte, low nibble first").  orc_encode_bits / orc_decode_reduce_bits.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (brute force over all 16 codes in float64, verbatim outliers, half-step
  * error bound, closed-form bit counts, Irwin-Hall variance of the summed
@@ -57,7 +65,7 @@
  * build's own choice and is only checked against its written description.
  *
  * Layouts here are dense (no row padding):
- *   outl  uint16 [T][k]          codes uint8 [T][ceil(r/2)]
+ *   outl  uint16 [T][k]          codes uint8 [T][ceil(r/2)]  (b bits: [T][ceil(r*b/8)])
  *   scale uint16 [T][ceil(r/G)]  zero  uint16 [T][ceil(r/G)]
  */
 #include <math.h>
@@ -376,6 +384,147 @@ int orc_decode_reduce(int N, int64_t T, int E, int k, int G,
                     float s = bf16_to_f32(scale[i][t * ng + c / G]);
                     float z = bf16_to_f32(zero[i][t * ng + c / G]);
                     float prod = (float)code * s; /* exact: 4 bits x 8 bits */
+                    x = prod + z;
+                }
+                if (accum == ORC_ACC_BF16) {
+                    x = round_to_bf16(x);
+                    acc = (i == 0) ? x : round_to_bf16(acc + x);
+                } else {
+                    acc = (i == 0) ? x : acc + x;
+                }
+            }
+            if (of)
+                of[j] = acc;
+            else
+                ob[j] = f32_to_bf16(acc);
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/* ---- other bit widths ---------------------------------------------------- */
+
+static int bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 5 || b == 6 || b == 8; }
+
+/* bit n of a row's code string is bit n%8 of byte n/8 */
+static void put_code(uint8_t *row, int64_t c, int b, unsigned code)
+{
+    for (int i = 0; i < b; ++i) {
+        int64_t n = (int64_t)b * c + i;
+        if ((code >> i) & 1u) row[n >> 3] |= (uint8_t)(1u << (n & 7));
+    }
+}
+
+static unsigned get_code(const uint8_t *row, int64_t c, int b)
+{
+    unsigned code = 0;
+    for (int i = 0; i < b; ++i) {
+        int64_t n = (int64_t)b * c + i;
+        code |= (unsigned)((row[n >> 3] >> (n & 7)) & 1u) << i;
+    }
+    return code;
+}
+
+/*
+ * orc_encode with b-bit codes (paper Sec. 4, Fig. 3: the number of bits of the
+ * quantised features is varied).  codes: uint8 [T][ceil(r*b/8)].
+ */
+int orc_encode_bits(const uint16_t *Y, int64_t T, int64_t ldY, int E, int k, int G, int bits,
+                    const int32_t *idx_sorted, uint16_t *outl, uint8_t *codes,
+                    uint16_t *scale, uint16_t *zero, int threads)
+{
+    if (!Y || T < 0 || E < 1 || k < 0 || k > E || G < 2 || (G & 1) || ldY < E || !bits_ok(bits))
+        return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !scale || !zero)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int64_t cb = ((int64_t)r * bits + 7) / 8;
+    int ng = (r + G - 1) / G;
+    float qmax = (float)((1 << bits) - 1);
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const uint16_t *y = Y + t * ldY;
+        for (int p = 0; p < k; ++p) outl[t * k + p] = y[idx_sorted[p]];
+        uint8_t *row = codes ? codes + t * cb : NULL;
+        if (row) memset(row, 0, (size_t)cb);
+        for (int g = 0; g < ng; ++g) {
+            int c0 = g * G;
+            int c1 = c0 + G < r ? c0 + G : r;
+            float mn = bf16_to_f32(y[comp[c0]]);
+            float mx = mn;
+            for (int c = c0 + 1; c < c1; ++c) {
+                float v = bf16_to_f32(y[comp[c]]);
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+            mn += 0.0f;
+            float span = mx - mn;
+            float s32 = span / qmax;
+            uint16_t sb = f32_to_bf16(s32);
+            float s = bf16_to_f32(sb);
+            zero[t * ng + g] = f32_bits_hi(mn);
+            if (s < 1e-30f) {
+                scale[t * ng + g] = 0;
+                continue;
+            }
+            scale[t * ng + g] = sb;
+            float inv = 1.0f / s;
+            for (int c = c0; c < c1; ++c) {
+                float v = bf16_to_f32(y[comp[c]]);
+                float d = v - mn;
+                float p = d * inv;
+                float q = rintf(p); /* ties to even */
+                if (q < 0.0f) q = 0.0f;
+                if (q > qmax) q = qmax;
+                put_code(row, c, bits, (unsigned)q);
+            }
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/* orc_decode_reduce with b-bit codes; everything else as there. */
+int orc_decode_reduce_bits(int N, int64_t T, int E, int k, int G, int bits,
+                           const int32_t *idx_sorted, const uint8_t *const *codes,
+                           const uint16_t *const *scale, const uint16_t *const *zero,
+                           const uint16_t *const *outl, int accum, int out_fp32,
+                           void *out, int threads)
+{
+    if (N < 1 || T < 0 || E < 1 || k < 0 || k > E || G < 2 || (G & 1) || !out || !bits_ok(bits))
+        return ORC_ERR_ARG;
+    if (accum != ORC_ACC_FP32 && accum != ORC_ACC_BF16) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !scale || !zero)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int64_t cb = ((int64_t)r * bits + 7) / 8;
+    int ng = (r + G - 1) / G;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float *of = out_fp32 ? (float *)out + t * E : NULL;
+        uint16_t *ob = out_fp32 ? NULL : (uint16_t *)out + t * E;
+        for (int col = 0; col < E; ++col) {
+            int is_outlier = col >= r;
+            int j = is_outlier ? idx_sorted[col - r] : comp[col];
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                float x;
+                if (is_outlier) {
+                    x = bf16_to_f32(outl[i][t * k + (col - r)]);
+                } else {
+                    unsigned code = get_code(codes[i] + t * cb, col, bits);
+                    float s = bf16_to_f32(scale[i][t * ng + col / G]);
+                    float z = bf16_to_f32(zero[i][t * ng + col / G]);
+                    float prod = (float)code * s; /* exact: at most 8 bits x 8 bits */
                     x = prod + z;
                 }
                 if (accum == ORC_ACC_BF16) {
