@@ -13,6 +13,7 @@ This script adds what a deployment asks next, one JSON line per section:
           HIP graph (every replay is checked against the eager result);
   large   the large prefill stress block (16 ranks, [16384 x 8192]) in its four variants, fp32
           accumulate, bf16 and fp32 output;
+  bits    the Llama-2-13B-shaped block at the other code widths (2, 3, 5, 6, 8 bits beside 4);
   static  the Llama-2-13B-shaped block in the static symmetric mode (per device and feature steps
           from calibration; only codes and selected features travel): encode of all ranks, of one
           rank, decode_reduce in both accumulate modes.
@@ -173,6 +174,37 @@ def section_large(tpq, wl, args):
             "note": "16 ranks x [16384 x 8192], fp32 accumulate; one buffer set (5.6 GB, far beyond the caches)"}
 
 
+def section_bits(tpq, wl, args):
+    w = wl.LLAMA_PREFILL
+    N, T, E = w.N, w.T, w.E
+    dev = "cuda"
+    idx = torch.from_numpy(idx_for(wl, w)).to(dev)
+    Yss = [wl.partial_sums(w, block=s, device=dev) for s in range(6)]
+    out = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+    rows = []
+    for b in (2, 3, 4, 5, 6, 8):
+        L = tpq.layout_init(E, w.k, w.G, b)
+        plan = tpq.plan_build(L, idx)
+        tpq.plan_check(L, plan)
+        sets = []
+        for Ys in Yss:
+            msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+            sets.append(dict(enc=tpq.encode_call(L, plan, Ys, msgs),
+                             dec_bf16=tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_BF16),
+                             dec_fp32=tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_FP32), keep=msgs))
+        W = L.wire_bytes_per_row
+        B_enc, B_dec = N * T * (2 * E + W), T * (N * W + 2 * E)
+        t = {k: timed([s[k] for s in sets], 30) / len(sets) for k in ("enc", "dec_bf16", "dec_fp32")}
+        rows.append({"bits": b, "payload_bits": round(tpq.payload_bits(L), 4), "wire_bits": round(tpq.wire_bits(L), 4),
+                     "us": {k: round(v, 2) for k, v in t.items()},
+                     "encode_GBps": round(B_enc / t["enc"] / 1e3, 1),
+                     "decode_reduce_GBps": {"bf16": round(B_dec / t["dec_bf16"] / 1e3, 1),
+                                            "fp32": round(B_dec / t["dec_fp32"] / 1e3, 1)}})
+        del sets
+    return {"section": "llama2_13b_prefill_code_widths", "widths": rows,
+            "note": "8 ranks x [2048 x 5120], k = 80, G = 128; launches back to back, 6 rotating buffer sets"}
+
+
 def section_static(tpq, wl, args):
     w = wl.LLAMA_PREFILL
     N, T, E = w.N, w.T, w.E
@@ -210,14 +242,14 @@ def section_static(tpq, wl, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sections", default="llama,gemma,large,static")
+    ap.add_argument("--sections", default="llama,gemma,large,static,bits")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")
     import paper_2411_07942_amd as tpq
     import workloads as wl
     table = {"llama": section_llama, "gemma": section_gemma, "large": section_large,
-             "static": section_static}
+             "static": section_static, "bits": section_bits}
     for name in args.sections.split(","):
         print(json.dumps(table[name](tpq, wl, args)), flush=True)
 

@@ -23,6 +23,15 @@
  *     x_hat = code * scale + zero
  * All arithmetic is IEEE binary32 without contraction.
  *
+ * Other code widths (Sec. 4, the experiment that varies the number of bits of the
+ * quantised features, Fig. 3): bits b in {2, 3, 5, 6, 8} beside 4, with 2^b - 1 in
+ * place of 15 everywhere above.  The codes of a row then form one little-endian bit
+ * string: code c occupies bits b*c .. b*c + b - 1, bit n of the string being bit
+ * n % 8 of byte n / 8 (for b = 4 that is the nibble layout below).  For these
+ * widths the kernels store whole chunks of 8 codes (b bytes; unused bits zero) and
+ * read 8 bytes from the start of each chunk, so pitch_codes is at least
+ * ceil(r/8)*b + 8, rounded up to 16.
+ *
  * Message of one device for one block = four row-major matrices:
  *     outl  bf16  [T][k]             pitch_outl  bytes per row
  *     codes u8    [T][ceil(r/2)]     pitch_codes bytes per row
@@ -61,7 +70,7 @@ extern "C" {
 #define TPQ_ERR_NULL (-1)        /* a required pointer is NULL                         */
 #define TPQ_ERR_SHAPE (-2)       /* a size is out of range or inconsistent             */
 #define TPQ_ERR_INDEX (-3)       /* indices unsorted, duplicated or out of range       */
-#define TPQ_ERR_UNSUPPORTED (-4) /* bits != 4, G not in {32,64,128,256}, bad mode      */
+#define TPQ_ERR_UNSUPPORTED (-4) /* bits not in {2,3,4,5,6,8}, G not in {32,64,128,256}, bad mode */
 #define TPQ_ERR_ALIGN (-5)       /* pointer or pitch alignment                         */
 #define TPQ_ERR_WORKSPACE (-6)   /* workspace / plan buffer too small                  */
 #define TPQ_ERR_HIP (-7)         /* a HIP call failed; see tpq_last_hip_error()        */
@@ -80,10 +89,10 @@ typedef struct tpq_layout {
     int32_t E;          /* features per row; multiple of 8, <= TPQ_MAX_E               */
     int32_t k;          /* features kept in bf16, 0 <= k <= E                          */
     int32_t G;          /* quantisation group size: 32, 64, 128 or 256                 */
-    int32_t bits;       /* code width; must be 4                                       */
+    int32_t bits;       /* code width b: 2, 3, 4, 5, 6 or 8                            */
     int32_t r;          /* E - k                                                       */
     int32_t ng;         /* ceil(r / G)                                                 */
-    int32_t code_bytes; /* ceil(r / 2)                                                 */
+    int32_t code_bytes; /* ceil(r * b / 8)                                             */
     int32_t reserved;
     int64_t pitch_codes; /* bytes per row of codes, multiple of 16, >= code_bytes      */
     int64_t pitch_meta;  /* bytes per row of scale and of zero, multiple of 16         */
@@ -94,7 +103,7 @@ typedef struct tpq_layout {
 /* [host] Derive the layout for (E, k, G, bits).  Pure host function. */
 int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits);
 
-/* Average bits per communicated value.  payload = (16k + 4r)/E is the paper's
+/* Average bits per communicated value.  payload = (16k + b*r)/E is the paper's
  * accounting (abstract; Sec. 4: k = floor(E/64) gives 4.1875 < 4.2); wire adds
  * the per-group scale and zero: 8 * wire_bytes_per_row / E. */
 double tpq_payload_bits(const tpq_layout *L);
@@ -182,7 +191,8 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
  * x * (1/step) clamped to -8..7, x_hat = code * step.  A feature whose
  * calibrated range vanishes (step < 1e-30) is sent as code 0 and comes back as 0.
  * The message is the codes section (same layout; the nibble is code + 8) and the
- * outl section: nothing else travels, 4 + 12k/E bits per value.
+ * outl section: nothing else travels, 4 + 12k/E bits per value.  This mode is built
+ * for 4-bit codes: a layout of another width is refused (TPQ_ERR_UNSUPPORTED).
  *
  * tpq_static_params turns the calibration state into the two tables the kernels
  * read, in the compacted feature order of `plan`:

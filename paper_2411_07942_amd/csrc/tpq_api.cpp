@@ -19,21 +19,32 @@ int hip_result(hipError_t e)
 
 static bool group_ok(int G) { return G == 32 || G == 64 || G == 128 || G == 256; }
 
+static bool bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 5 || b == 6 || b == 8; }
+
 static int64_t round16(int64_t v) { return (v + 15) / 16 * 16; }
+
+// Bytes of a row of codes, and the least pitch: 4 bits: the last 32-bit word is stored
+// whole; other widths: whole chunks of 8 codes are stored, and the decoder reads 8 bytes
+// from the start of every chunk.
+static int64_t code_bytes_of(int r, int bits) { return (static_cast<int64_t>(r) * bits + 7) / 8; }
+static int64_t min_pitch_codes(int r, int bits)
+{
+    if (bits == 4) return round16(code_bytes_of(r, 4));
+    return r > 0 ? round16(static_cast<int64_t>(chunks_of(r)) * bits + 8) : 0;
+}
 
 int check_layout(const tpq_layout *L)
 {
     if (!L) return TPQ_ERR_NULL;
-    if (L->bits != 4 || !group_ok(L->G)) return TPQ_ERR_UNSUPPORTED;
+    if (!bits_ok(L->bits) || !group_ok(L->G)) return TPQ_ERR_UNSUPPORTED;
     if (L->E < 8 || L->E > TPQ_MAX_E || (L->E % 8) != 0) return TPQ_ERR_SHAPE;
     if (L->k < 0 || L->k > L->E) return TPQ_ERR_SHAPE;
     const int r = L->E - L->k;
-    if (L->r != r || L->ng != (r + L->G - 1) / L->G || L->code_bytes != (r + 1) / 2)
+    if (L->r != r || L->ng != (r + L->G - 1) / L->G || L->code_bytes != code_bytes_of(r, L->bits))
         return TPQ_ERR_SHAPE;
     if (L->wire_bytes_per_row != 2LL * L->k + L->code_bytes + 4LL * L->ng) return TPQ_ERR_SHAPE;
     if ((L->pitch_codes % 16) || (L->pitch_meta % 16) || (L->pitch_outl % 16)) return TPQ_ERR_ALIGN;
-    // the last 32-bit word of a row of codes is stored whole
-    if (L->pitch_codes < round16(L->code_bytes) || L->pitch_meta < 2LL * L->ng ||
+    if (L->pitch_codes < min_pitch_codes(r, L->bits) || L->pitch_meta < 2LL * L->ng ||
         L->pitch_outl < 2LL * L->k)
         return TPQ_ERR_SHAPE;
     return TPQ_OK;
@@ -48,7 +59,7 @@ extern "C" {
 int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits)
 {
     if (!L) return TPQ_ERR_NULL;
-    if (bits != 4 || !group_ok(G)) return TPQ_ERR_UNSUPPORTED;
+    if (!bits_ok(bits) || !group_ok(G)) return TPQ_ERR_UNSUPPORTED;
     if (E < 8 || E > TPQ_MAX_E || (E % 8) != 0 || k < 0 || k > E) return TPQ_ERR_SHAPE;
     memset(L, 0, sizeof *L);
     L->E = E;
@@ -57,8 +68,8 @@ int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits)
     L->bits = bits;
     L->r = E - k;
     L->ng = (L->r + G - 1) / G;
-    L->code_bytes = (L->r + 1) / 2;
-    L->pitch_codes = round16(L->code_bytes);
+    L->code_bytes = static_cast<int32_t>(code_bytes_of(L->r, bits));
+    L->pitch_codes = min_pitch_codes(L->r, bits);
     L->pitch_meta = round16(2LL * L->ng);
     L->pitch_outl = round16(2LL * k);
     L->wire_bytes_per_row = 2LL * k + L->code_bytes + 4LL * L->ng;
@@ -68,7 +79,7 @@ int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits)
 double tpq_payload_bits(const tpq_layout *L)
 {
     if (!L || L->E <= 0) return 0.0;
-    return (16.0 * L->k + 4.0 * L->r) / L->E;
+    return (16.0 * L->k + static_cast<double>(L->bits) * L->r) / L->E;
 }
 
 double tpq_wire_bits(const tpq_layout *L)
@@ -227,6 +238,8 @@ int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y, 
     a.n_ranks = n_ranks;
     a.T = T; a.ldY = ldY;
     a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.bits = L->bits;
+    a.qmax = static_cast<float>((1 << L->bits) - 1);
     return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream));
 }
 
@@ -261,6 +274,7 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
     a.T = T; a.ldOut = ldOut;
     a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
     a.out = out;
+    a.bits = L->bits;
     return launch_decode(a, pc, ps, pz, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -277,6 +291,7 @@ int tpq_static_params(const tpq_layout *L, const void *plan, const float *m, con
 {
     int rc = check_layout(L);
     if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS) return TPQ_ERR_SHAPE;
     if (L->r == 0) return TPQ_OK;
     if (!plan || !m || !M || !step || !inv) return TPQ_ERR_NULL;
@@ -290,6 +305,7 @@ int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *con
 {
     int rc = check_layout(L);
     if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldY < L->E) return TPQ_ERR_SHAPE;
     if (T * n_ranks > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
     if ((ldY % 8) != 0) return TPQ_ERR_ALIGN;
@@ -315,6 +331,8 @@ int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *con
     a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
     a.inv_c = inv;
     a.static_stride = 8 * a.chunks_padded;
+    a.bits = 4;
+    a.qmax = 15.0f;
     return launch_encode(a, pY, pc, none, none, po, static_cast<hipStream_t>(stream));
 }
 
@@ -325,6 +343,7 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
 {
     int rc = check_layout(L);
     if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
     if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
@@ -352,6 +371,7 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
     a.out = out;
     a.step_c = quant ? step : nullptr;
     a.static_stride = 8 * a.chunks_padded;
+    a.bits = 4;
     return launch_decode(a, pc, none, none, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
 

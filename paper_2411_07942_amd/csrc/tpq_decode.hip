@@ -17,6 +17,15 @@ __device__ __forceinline__ float round_via_bf16(float x)
     return __uint_as_float(pack_bf16x2(0.0f, x));
 }
 
+// The 8 B-bit fields of a 64-bit word as floats: field e at bits B*e .. B*e + B - 1.
+template <int B>
+__device__ __forceinline__ void unpack_codes(uint64_t w, float (&c)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        c[e] = static_cast<float>(static_cast<uint32_t>(w >> (B * e)) & ((1u << B) - 1u));
+}
+
 // acc <- acc (+) x for 8 features at once, in the requested arithmetic
 template <int ACC>
 __device__ __forceinline__ void accumulate8(float (&acc)[8], float (&x)[8], bool first)
@@ -138,7 +147,11 @@ __device__ __forceinline__ void store_pass(u32x4 *st, const float (&acc)[8], uin
 // its column.
 // grid: x = row, y = groups of 4 waves.
 // ---------------------------------------------------------------------------
-template <int LPG, int ACC, int OUT>
+//
+// GEN selects code widths other than 4 bits (Sec. 4, the experiment that varies the bits
+// of the quantised features): a chunk's 8 codes are b bytes at byte chunk * b of the row,
+// fetched with one 64-bit load at that byte (the row's pitch leaves room behind the last).
+template <int LPG, int ACC, int OUT, bool GEN>
 __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs codesp, RankPtrs scalep,
                                                      RankPtrs zerop, RankPtrs outlp)
 {
@@ -200,7 +213,8 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     const uint32_t e1 = 64u + lane < nall ? entries[64u + lane] : 0u;
     // One 32-bit byte offset per section serves every rank (the host keeps
     // T * pitch below 2^31 per launch): the rank only changes the scalar base.
-    const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
+    const uint32_t off_codes = t * static_cast<uint32_t>(a.pitch_codes) +
+                               (GEN ? static_cast<uint32_t>(a.bits) : 4u) * min(chunk, chunks - 1u);
     const uint32_t off_meta = t * static_cast<uint32_t>(a.pitch_meta) + 2u * g;
     float acc[8];
 
@@ -210,14 +224,19 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     auto batch = [&](uint32_t i0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         uint32_t w[8], sb[8], zb[8];
+        uint64_t wq[8];  // GEN
         const void *const *pc = codesp.p + i0;
         const void *const *ps = scalep.p + i0;
         const void *const *pz = zerop.p + i0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
-            w[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
-                static_cast<const uint8_t *>(pc[i]) + off_codes));
+            if constexpr (GEN)
+                wq[j] = __builtin_nontemporal_load(reinterpret_cast<const u64_a1 *>(
+                    static_cast<const uint8_t *>(pc[i]) + off_codes));
+            else
+                w[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                    static_cast<const uint8_t *>(pc[i]) + off_codes));
             sb[j] = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(ps[i]) + off_meta);
             zb[j] = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(pz[i]) + off_meta);
         }
@@ -228,13 +247,26 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
                 // one code per byte, so that each converts with a single byte-to-float
                 // instruction (the masks are hidden from the optimiser, which would
                 // otherwise fold them into separate bit-field extracts)
-                uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
-                asm volatile("" : "+v"(lo), "+v"(hi));
                 float x[8];
+                if constexpr (GEN) {
+                    float c[8];
+                    switch (a.bits) {
+                    case 2: unpack_codes<2>(wq[j], c); break;
+                    case 3: unpack_codes<3>(wq[j], c); break;
+                    case 5: unpack_codes<5>(wq[j], c); break;
+                    case 6: unpack_codes<6>(wq[j], c); break;
+                    default: unpack_codes<8>(wq[j], c); break;
+                    }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    x[2 * e] = __builtin_fmaf(static_cast<float>((lo >> (8 * e)) & 0xFFu), sc, ze);
-                    x[2 * e + 1] = __builtin_fmaf(static_cast<float>((hi >> (8 * e)) & 0xFFu), sc, ze);
+                    for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(c[e], sc, ze);  // product exact
+                } else {
+                    uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
+                    asm volatile("" : "+v"(lo), "+v"(hi));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        x[2 * e] = __builtin_fmaf(static_cast<float>((lo >> (8 * e)) & 0xFFu), sc, ze);
+                        x[2 * e + 1] = __builtin_fmaf(static_cast<float>((hi >> (8 * e)) & 0xFFu), sc, ze);
+                    }
                 }
                 accumulate8<ACC>(acc, x, i0 + j == 0);
             }
@@ -411,7 +443,10 @@ static void launch_rows(int rpw, dim3 grid, hipStream_t s, const DecodeArgs &a, 
         else
             k_decode_static<ACC, OUT, 1><<<grid, 256, 0, s>>>(a, codes, outl);
     } else {
-        k_decode_pass<LPG, ACC, OUT><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+        if (a.bits != 4)
+            k_decode_pass<LPG, ACC, OUT, true><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+        else
+            k_decode_pass<LPG, ACC, OUT, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
     }
 }
 

@@ -34,6 +34,12 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 
+// scalars at byte alignment (code widths other than 4 bits put a chunk's codes at any byte)
+typedef uint16_t u16_a1 __attribute__((aligned(1)));
+typedef uint32_t u32_a1 __attribute__((aligned(1)));
+typedef uint32_t u32_a2 __attribute__((aligned(2)));
+typedef uint64_t u64_a1 __attribute__((aligned(1)));
+
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // two floats rounded to bf16 (nearest even, one hardware instruction), packed

@@ -83,6 +83,20 @@ __device__ __forceinline__ float reciprocal_of_scale(float s)
 // windows per 64 slots instead of one per pass, and scale / zero of all the task's
 // groups collected through LDS into one store each.
 // ---------------------------------------------------------------------------
+// Eight codes, one per byte of (lo, hi) in feature order, as B-bit fields of a 64-bit
+// word: code e at bits B*e .. B*e + B - 1.
+template <int B>
+__device__ __forceinline__ uint64_t pack_codes(uint32_t lo, uint32_t hi)
+{
+    uint64_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t c = ((e < 4 ? lo : hi) >> (8 * (e & 3))) & 0xFFu;
+        w |= static_cast<uint64_t>(c) << (B * e);
+    }
+    return w;
+}
+
 template <int P>
 struct DirectOcc {  // waves per SIMD the register budget is set for
     static constexpr int value = 8;
@@ -93,7 +107,11 @@ struct DirectOcc {  // waves per SIMD the register budget is set for
 // Precision Features"): the reciprocal step of every (device, feature) comes from a
 // table in compacted order, nothing is measured per group, and only codes and selected
 // features are written.  Everything up to the features in registers is shared.
-template <int LPG, int P, bool STATIC>
+//
+// GEN selects code widths other than 4 bits (Sec. 4, the experiment that varies the
+// bits of the quantised features): 2^b - 1 steps over the group's range, and the 8
+// codes of a chunk are b bytes of the row's little-endian bit string.
+template <int LPG, int P, bool STATIC, bool GEN = false>
 __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     EncodeArgs a, RankPtrs Yp, RankPtrs codesp, RankPtrs scalep, RankPtrs zerop, RankPtrs outlp)
 {
@@ -246,6 +264,7 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
         static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
         static_cast<int64_t>(t) * a.pitch_codes);
     uint32_t w[P];
+    uint64_t w64[P];  // GEN
     if constexpr (STATIC) {
         // code = clamp(rint(x * inv), -8, 7), sent as code + 8.  The product is rounded
         // to fp32 before the integer rounding (a fused multiply-add would round once
@@ -319,7 +338,7 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
         for (int p = 0; p < P; ++p) {
             mn[p] = mn[p] + 0.0f;  // a zero minimum is stored as +0
             const float span = mx[p] - mn[p];
-            const float s32 = div_by_15(span);
+            const float s32 = GEN ? span / a.qmax : div_by_15(span);  // (IEEE division)
             const uint32_t sb = pack_bf16x2(s32, s32) & 0xFFFFu;
             const float s = bf16_bits_to_f32(sb);
             const bool constant = s < 1e-30f;
@@ -378,14 +397,69 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
                     const float df = x - mn[p];
                     pr[e] = df * inv[p];
                 }
-                uint32_t b = __builtin_amdgcn_cvt_pk_u8_f32(pr[1], 0u, 0u);
-                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[0], 1u, b);
-                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[3], 2u, b);
-                b = __builtin_amdgcn_cvt_pk_u8_f32(pr[2], 3u, b);
-                h[half] = (b << 12) | b;
+                if constexpr (GEN) {
+                    // one code per byte, in feature order (the conversion saturates at 255,
+                    // which is the clamp the 8-bit width needs; narrower widths cannot overshoot)
+                    uint32_t b = __builtin_amdgcn_cvt_pk_u8_f32(pr[0], 0u, 0u);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[1], 1u, b);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[2], 2u, b);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[3], 3u, b);
+                    h[half] = b;
+                } else {
+                    uint32_t b = __builtin_amdgcn_cvt_pk_u8_f32(pr[1], 0u, 0u);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[0], 1u, b);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[3], 2u, b);
+                    b = __builtin_amdgcn_cvt_pk_u8_f32(pr[2], 3u, b);
+                    h[half] = (b << 12) | b;
+                }
             }
-            w[p] = __builtin_amdgcn_perm(h[1], h[0], 0x07050301u);
+            if constexpr (GEN) {
+                switch (a.bits) {
+                case 2: w64[p] = pack_codes<2>(h[0], h[1]); break;
+                case 3: w64[p] = pack_codes<3>(h[0], h[1]); break;
+                case 5: w64[p] = pack_codes<5>(h[0], h[1]); break;
+                case 6: w64[p] = pack_codes<6>(h[0], h[1]); break;
+                default: w64[p] = pack_codes<8>(h[0], h[1]); break;
+                }
+            } else {
+                w[p] = __builtin_amdgcn_perm(h[1], h[0], 0x07050301u);
+            }
         }
+    }
+    if constexpr (GEN) {
+        // b bytes per chunk at byte chunk * b of the row (the row's pitch has room for whole
+        // chunks); a ragged last chunk's unused bits are zero
+        uint8_t *cb = reinterpret_cast<uint8_t *>(codes);
+        const uint32_t b = static_cast<uint32_t>(a.bits);
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t chunk = (pass0 + p) * 64u + ln;
+            uint64_t wv = w64[p];
+            if (last_seg) {
+                const int n_valid = a.r - 8 * static_cast<int>(chunk);
+                if (n_valid < 8 && n_valid > 0) wv &= (1ull << (b * static_cast<uint32_t>(n_valid))) - 1ull;
+                if (chunk >= static_cast<uint32_t>(a.chunks)) continue;
+            }
+            uint8_t *dst = cb + chunk * b;
+            const uint32_t lo = static_cast<uint32_t>(wv), hi = static_cast<uint32_t>(wv >> 32);
+            switch (b) {
+            case 2: *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(lo); break;
+            case 3:
+                *reinterpret_cast<u16_a1 *>(dst) = static_cast<uint16_t>(lo);
+                dst[2] = static_cast<uint8_t>(lo >> 16);
+                break;
+            case 5:
+                *reinterpret_cast<u32_a1 *>(dst) = lo;
+                dst[4] = static_cast<uint8_t>(hi);
+                break;
+            case 6:
+                *reinterpret_cast<u32_a2 *>(dst) = lo;
+                *reinterpret_cast<uint16_t *>(dst + 4) = static_cast<uint16_t>(hi);
+                break;
+            default: *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi); break;
+            }
+        }
+        return;
     }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -400,17 +474,17 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     }
 }
 
-template <int LPG, int P, bool STATIC>
+template <int LPG, int P, bool STATIC, bool GEN>
 static hipError_t launch_direct_lp(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                                    const RankPtrs &scale, const RankPtrs &zero,
                                    const RankPtrs &outl, size_t lds, dim3 grid, hipStream_t s)
 {
     hipError_t e = hipSuccess;
     if (lds > 65536)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC, GEN>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
-    k_encode_direct<LPG, P, STATIC><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl);
+    k_encode_direct<LPG, P, STATIC, GEN><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl);
     return hipGetLastError();
 }
 
@@ -440,6 +514,7 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
     }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
     const bool is_static = a.inv_c != nullptr;
+    const bool is_gen = a.bits != 4;  // (never together with the static mode: the host refuses that)
     const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + (is_static ? 0u : 4u * (64 * P / lpg)));
 
     // task numbers of a rank stay below 2^32 / segs (the kernel divides by multiplying)
@@ -460,7 +535,10 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         const dim3 grid(static_cast<unsigned>((a.n_tasks + 3) / 4), static_cast<unsigned>(a.n_ranks));
 #define TPQ_DIRECT_P(LPG, PP)                                                                       \
     case PP:                                                                                        \
-        e = launch_direct_lp<LPG, PP, LPG == 0>(a, Y, codes, scale, zero, outl, lds, grid, s);      \
+        e = is_gen ? launch_direct_lp<(LPG == 0 ? 4 : LPG), PP, false, true>(a, Y, codes, scale, zero, outl, \
+                                                                             lds, grid, s)            \
+                   : launch_direct_lp<LPG, PP, LPG == 0, false>(a, Y, codes, scale, zero, outl, lds,  \
+                                                                grid, s);                             \
         break;
 #define TPQ_DIRECT(LPG)                                                                      \
     switch (P) {                                                                             \

@@ -204,6 +204,8 @@ struct EncodeArgs {
     int64_t n_tasks;  // T * segs (per rank)
     int32_t dslots;   // slots in the plan's tables of the direct kernel
     uint32_t segs_magic;  // 2^32 / segs + 1: task / segs = mulhi(task, segs_magic)
+    int32_t bits;  // code width
+    float qmax;    // 2^bits - 1
     // static symmetric mode: reciprocal steps, fp32 [n_ranks][static_stride] in compacted order
     const float *inv_c;
     int32_t static_stride;
@@ -218,6 +220,7 @@ struct DecodeArgs {
     int64_t T, ldOut;
     int64_t pitch_codes, pitch_meta, pitch_outl;
     void *out;
+    int32_t bits;  // code width
     // static symmetric mode: steps, fp32 [n_ranks][static_stride] in compacted order
     const float *step_c;
     int32_t static_stride;

@@ -49,13 +49,29 @@ def test_layout_closed_forms(E, k, G, W, pb, wb):
     assert tpq.plan_bytes(L) >= 64 + 4 * k + 2 * (E - k)
 
 
+@pytest.mark.parametrize("b", [2, 3, 4, 5, 6, 8])
+@pytest.mark.parametrize("E,k,G", [(512, 8, 128), (5120, 80, 128), (1032, 1, 64), (64, 64, 32)])
+def test_layout_other_widths(E, k, G, b):
+    """b bits for the quantised features (Sec. 4, Fig. 3): b + (16 - b) k / E per value."""
+    L = tpq.layout_init(E, k, G, b)
+    r = E - k
+    assert (L.bits, L.r, L.ng, L.code_bytes) == (b, r, -(-r // G), (r * b + 7) // 8)
+    assert tpq.payload_bits(L) == b + (16 - b) * k / E
+    assert L.wire_bytes_per_row == 2 * k + L.code_bytes + 4 * L.ng
+    assert L.pitch_codes % 16 == 0 and L.pitch_codes >= L.code_bytes
+    if b != 4 and r > 0:     # whole chunks are stored, 8 bytes are read from the start of each
+        assert L.pitch_codes >= -(-r // 8) * b + 8
+
+
 def test_k_floor_E_over_64_is_under_4p2_bits():
     for E in (512, 4096, 4608, 5120, 8192, 16384):
         assert tpq.payload_bits(tpq.layout_init(E, E // 64, 128)) < 4.2
 
 
 @pytest.mark.parametrize("args,code", [
-    ((512, 8, 128, 8), tpq.ERR_UNSUPPORTED),
+    ((512, 8, 128, 7), tpq.ERR_UNSUPPORTED),
+    ((512, 8, 128, 1), tpq.ERR_UNSUPPORTED),
+    ((512, 8, 128, 16), tpq.ERR_UNSUPPORTED),
     ((512, 8, 100, 4), tpq.ERR_UNSUPPORTED),
     ((512, 8, 16, 4), tpq.ERR_UNSUPPORTED),
     ((500, 8, 128, 4), tpq.ERR_SHAPE),
