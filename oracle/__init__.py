@@ -56,6 +56,8 @@ def _load():
         lib.orc_encode.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp,
                                           i32, i32, vp, i32]
+        lib.orc_decode_reduce_fused.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp,
+                                                i32, i32, vp, i32]
         lib.orc_encode_bits.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce_bits.argtypes = [i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
                                                i32, i32, vp, i32]
@@ -195,6 +197,44 @@ def decode_reduce(msgs, idx_sorted, E: int, G: int, accum: int = ACC_FP32,
                                             outl, accum, int(bool(out_fp32)), _ptr(out), threads)
     if rc:
         raise ValueError("orc_decode_reduce: bad arguments")
+    return out
+
+
+def decode_reduce_fused(msgs, idx_sorted, E: int, G: int, addend=None, bias=None,
+                        accum: int = ACC_FP32, out_fp32: bool = False, threads: int = 1) -> np.ndarray:
+    """decode_reduce, then + addend (bf16 bits [T,E]) and + bias (bf16 bits [E]) as further terms
+    of the same accumulation (Sec. 2: the sum over the devices plus the bias)."""
+    N = len(msgs)
+    idx_sorted = np.ascontiguousarray(idx_sorted, dtype=np.int32)
+    k = idx_sorted.shape[0]
+    T = msgs[0].codes.shape[0] if k < E else msgs[0].outl.shape[0]
+    r, cb, ng = dims(E, k, G)
+    keep = []
+
+    def table(name, dtype, shape):
+        arr = (ctypes.c_void_p * N)()
+        for i, mg in enumerate(msgs):
+            a = np.ascontiguousarray(getattr(mg, name), dtype=dtype)
+            assert a.shape == shape, (name, a.shape, shape)
+            keep.append(a)
+            arr[i] = a.ctypes.data
+        return arr
+
+    codes = table("codes", np.uint8, (T, cb))
+    scale = table("scale", np.uint16, (T, ng))
+    zero = table("zero", np.uint16, (T, ng))
+    outl = table("outl", np.uint16, (T, k))
+    add = None if addend is None else _u16(addend)
+    bia = None if bias is None else np.ascontiguousarray(bias, dtype=np.uint16)
+    assert add is None or add.shape == (T, E)
+    assert bia is None or bia.shape == (E,)
+    out = np.empty((T, E), np.float32 if out_fp32 else np.uint16)
+    rc = _load().orc_decode_reduce_fused(N, T, E, k, G, _ptr(idx_sorted), codes, scale, zero, outl,
+                                         None if add is None else _ptr(add), E,
+                                         None if bia is None else _ptr(bia),
+                                         accum, int(bool(out_fp32)), _ptr(out), threads)
+    if rc:
+        raise ValueError("orc_decode_reduce_fused: bad arguments")
     return out
 
 

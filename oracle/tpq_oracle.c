@@ -54,6 +54,13 @@
  *   bit n of the string being bit n%8 of byte n/8 (for b = 4 this is "two codes
  *   per byte, low nibble first").  orc_encode_bits / orc_decode_reduce_bits.
  *
+ *   fused epilogue (paper Sec. 2: the block's output is the sum over the
+ *   devices plus the bias, f(x) = [sum_i f^(i)(x^(i))] + b): orc_decode_reduce_fused
+ *   adds, after the sum over the messages, an optional addend row (bf16 [T][E]:
+ *   a residual, or the device's own partial sum when its message is left out)
+ *   and then an optional bias (bf16 [E]), each as one more term of the same
+ *   accumulation (fp32 add, or bf16-rounded add in the literal bf16 chain).
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (brute force over all 16 codes in float64, verbatim outliers, half-step
  * error bound, closed-form bit counts, Irwin-Hall variance of the summed
@@ -392,6 +399,81 @@ int orc_decode_reduce(int N, int64_t T, int E, int k, int G,
                 } else {
                     acc = (i == 0) ? x : acc + x;
                 }
+            }
+            if (of)
+                of[j] = acc;
+            else
+                ob[j] = f32_to_bf16(acc);
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+/* ---- decode + reduce with the block's epilogue --------------------------- */
+
+/*
+ * orc_decode_reduce (4-bit codes) followed, per element, by
+ *   acc = acc (+) addend[t][j]   if addend != NULL  (bf16 [T][ldAdd])
+ *   acc = acc (+) bias[j]        if bias   != NULL  (bf16 [E])
+ * in this order, (+) being the accumulation's own addition: fp32, or fp32 rounded to
+ * bf16 in the literal bf16 chain.  Sec. 2: f(x) = [sum_i f^(i)(x^(i))] + b.
+ */
+int orc_decode_reduce_fused(int N, int64_t T, int E, int k, int G,
+                            const int32_t *idx_sorted, const uint8_t *const *codes,
+                            const uint16_t *const *scale, const uint16_t *const *zero,
+                            const uint16_t *const *outl, const uint16_t *addend, int64_t ldAdd,
+                            const uint16_t *bias, int accum, int out_fp32, void *out,
+                            int threads)
+{
+    if (N < 1 || T < 0 || E < 1 || k < 0 || k > E || G < 2 || (G & 1) || !out) return ORC_ERR_ARG;
+    if (accum != ORC_ACC_FP32 && accum != ORC_ACC_BF16) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !scale || !zero)) return ORC_ERR_ARG;
+    if (addend && ldAdd < E) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int cb = (r + 1) / 2;
+    int ng = (r + G - 1) / G;
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float *of = out_fp32 ? (float *)out + t * E : NULL;
+        uint16_t *ob = out_fp32 ? NULL : (uint16_t *)out + t * E;
+        for (int col = 0; col < E; ++col) {
+            int is_outlier = col >= r;
+            int j = is_outlier ? idx_sorted[col - r] : comp[col];
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                float x;
+                if (is_outlier) {
+                    x = bf16_to_f32(outl[i][t * k + (col - r)]);
+                } else {
+                    uint8_t byte = codes[i][t * cb + (col >> 1)];
+                    unsigned code = (col & 1) ? (byte >> 4) : (byte & 0x0Fu);
+                    float sc = bf16_to_f32(scale[i][t * ng + col / G]);
+                    float z = bf16_to_f32(zero[i][t * ng + col / G]);
+                    float prod = (float)code * sc;
+                    x = prod + z;
+                }
+                if (accum == ORC_ACC_BF16) {
+                    x = round_to_bf16(x);
+                    acc = (i == 0) ? x : round_to_bf16(acc + x);
+                } else {
+                    acc = (i == 0) ? x : acc + x;
+                }
+            }
+            if (addend) {
+                float a = bf16_to_f32(addend[t * ldAdd + j]);
+                acc = acc + a;
+                if (accum == ORC_ACC_BF16) acc = round_to_bf16(acc);
+            }
+            if (bias) {
+                float b = bf16_to_f32(bias[j]);
+                acc = acc + b;
+                if (accum == ORC_ACC_BF16) acc = round_to_bf16(acc);
             }
             if (of)
                 of[j] = acc;
