@@ -14,6 +14,8 @@ This script adds what a deployment asks next, one JSON line per section:
   large   the large prefill stress block (16 ranks, [16384 x 8192]) in its four variants, fp32
           accumulate, bf16 and fp32 output;
   bits    the Llama-2-13B-shaped block at the other code widths (2, 3, 5, 6, 8 bits beside 4);
+  fused   the Llama-2-13B-shaped block: decode_reduce with the residual and bias added inside the
+          kernel, beside decode_reduce followed by two elementwise additions;
   static  the Llama-2-13B-shaped block in the static symmetric mode (per device and feature steps
           from calibration; only codes and selected features travel): encode of all ranks, of one
           rank, decode_reduce in both accumulate modes.
@@ -205,6 +207,38 @@ def section_bits(tpq, wl, args):
             "note": "8 ranks x [2048 x 5120], k = 80, G = 128; launches back to back, 6 rotating buffer sets"}
 
 
+def section_fused(tpq, wl, args):
+    w = wl.LLAMA_PREFILL
+    N, T, E = w.N, w.T, w.E
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
+    tpq.plan_check(L, plan)
+    bias = torch.randn(E, device=dev).to(torch.bfloat16)
+    sets = []
+    for s in range(6):
+        Ys = wl.partial_sums(w, block=s, device=dev)
+        msgs = [tpq.Message(L, T, dev) for _ in range(N)]
+        tpq.encode(L, plan, Ys, msgs)
+        out = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        res = torch.randn((T, E), device=dev).to(torch.bfloat16)
+        plain = tpq.decode_reduce_call(L, plan, msgs, out, tpq.ACC_BF16)
+
+        def unfused(plain=plain, out=out, res=res):
+            plain()
+            out.add_(res)
+            out.add_(bias)
+        sets.append(dict(plain=plain, unfused=unfused,
+                         fused_bf16=tpq.decode_reduce_fused_call(L, plan, msgs, out, res, bias, tpq.ACC_BF16),
+                         fused_fp32=tpq.decode_reduce_fused_call(L, plan, msgs, out, res, bias, tpq.ACC_FP32),
+                         keep=(Ys, msgs, out, res)))
+    t = {k: round(timed([s[k] for s in sets], 40) / len(sets), 2)
+         for k in ("plain", "unfused", "fused_bf16", "fused_fp32")}
+    return {"section": "llama2_13b_prefill_fused_epilogue", "us": t,
+            "note": "decode_reduce (bf16 chain) alone; followed by two torch additions (residual, bias); "
+                    "tpq_decode_reduce_fused with both, bf16 chain and fp32 accumulate"}
+
+
 def section_static(tpq, wl, args):
     w = wl.LLAMA_PREFILL
     N, T, E = w.N, w.T, w.E
@@ -242,14 +276,14 @@ def section_static(tpq, wl, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sections", default="llama,gemma,large,static,bits")
+    ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")
     import paper_2411_07942_amd as tpq
     import workloads as wl
     table = {"llama": section_llama, "gemma": section_gemma, "large": section_large,
-             "static": section_static, "bits": section_bits}
+             "static": section_static, "bits": section_bits, "fused": section_fused}
     for name in args.sections.split(","):
         print(json.dumps(table[name](tpq, wl, args)), flush=True)
 

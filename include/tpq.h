@@ -182,6 +182,25 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
                       int accum, int out_dtype, void *out, int64_t ldOut,
                       void *stream);
 
+/* tpq_decode_reduce followed by the block's epilogue (Sec. 2: the output of a
+ * row-parallel block is the sum over the devices plus the bias,
+ * f(x) = [sum_i f^(i)(x^(i))] + b), inside the same kernel:
+ *     out[t][j] = ((sum over the n_ranks messages) (+) addend[t][j]) (+) bias[j]
+ * where (+) is the accumulation's own addition (fp32; in TPQ_ACC_BF16 every result is
+ * rounded to bf16), the terms entering in this order.
+ *   addend  [device] bf16 [T][ldAdd] or NULL: a residual -- or the device's own partial
+ *           sum, when the caller leaves that device's message out of the n_ranks
+ *           messages (its own data then carries no quantisation error); ldAdd >= E;
+ *           rows need 2-byte alignment only
+ *   bias    [device] bf16 [E] or NULL
+ * Everything else as tpq_decode_reduce.  4-bit layouts only (TPQ_ERR_UNSUPPORTED
+ * otherwise).  With both NULL the result equals tpq_decode_reduce's. */
+int tpq_decode_reduce_fused(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
+                            const uint8_t *const *codes, const uint16_t *const *scale,
+                            const uint16_t *const *zero, const uint16_t *const *outl,
+                            const uint16_t *addend, int64_t ldAdd, const uint16_t *bias, int accum,
+                            int out_dtype, void *out, int64_t ldOut, void *stream);
+
 /* ---- static symmetric mode (the paper's own quantiser, Sec. 3) --------------
  * "Calibration": every feature on every device has static, independent
  * quantisation parameters; "Selecting High Precision Features": the range is

@@ -32,7 +32,7 @@ EXPORTS = [
     "tpq_plan_bytes", "tpq_plan_build", "tpq_plan_check",
     "tpq_calibrate_workspace_bytes", "tpq_calibrate",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
-    "tpq_encode", "tpq_decode_reduce",
+    "tpq_encode", "tpq_decode_reduce", "tpq_decode_reduce_fused",
     "tpq_static_table_floats", "tpq_static_params", "tpq_encode_static", "tpq_decode_reduce_static",
 ]
 
@@ -89,6 +89,8 @@ def _load():
     lib.tpq_calibrate_finalize.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.tpq_encode.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, vp]
     lib.tpq_decode_reduce.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, c_int, c_int, vp, i64, vp]
+    lib.tpq_decode_reduce_fused.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, vp, i64, vp, c_int, c_int,
+                                            vp, i64, vp]
     lib.tpq_static_table_floats.argtypes = [LP]
     lib.tpq_static_table_floats.restype = sz
     lib.tpq_static_params.argtypes = [LP, vp, vp, vp, c_int, vp, vp, vp]
@@ -275,6 +277,39 @@ def decode_reduce(L: Layout, plan: torch.Tensor, msgs: Sequence[Message], out: t
                   accum: int = ACC_FP32, stream=None) -> None:
     """Dequantise and add msgs[0..n-1] into out ([T,E] bf16 or fp32)."""
     decode_reduce_call(L, plan, msgs, out, accum)(stream)
+
+
+def decode_reduce_fused_call(L: Layout, plan: torch.Tensor, msgs: Sequence[Message], out: torch.Tensor,
+                             addend: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                             accum: int = ACC_FP32):
+    """Marshal a tpq_decode_reduce_fused call once; the returned function(stream=None) issues it.
+    addend: bf16 [T, E] (row stride free) or None; bias: bf16 [E] or None."""
+    lib = _load()
+    n = len(msgs)
+    T = out.shape[0]
+    out_dtype = OUT_FP32 if out.dtype == torch.float32 else OUT_BF16
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    ldOut = out.stride(0) if T > 1 else max(L.E, out.stride(0))
+    ldAdd = 0
+    if addend is not None:
+        assert addend.dtype == torch.bfloat16 and addend.shape == (T, L.E) and addend.stride(1) == 1
+        ldAdd = addend.stride(0) if T > 1 else max(L.E, addend.stride(0))
+    if bias is not None:
+        assert bias.dtype == torch.bfloat16 and bias.shape == (L.E,) and bias.is_contiguous()
+    args = (ctypes.byref(L), _ptr(plan), n, T,
+            _ptr_array([m.codes for m in msgs], n), _ptr_array([m.scale for m in msgs], n),
+            _ptr_array([m.zero for m in msgs], n), _ptr_array([m.outl for m in msgs], n),
+            _ptr(addend), ldAdd, _ptr(bias), accum, out_dtype, _ptr(out), ldOut)
+    keep = (L, plan, list(msgs), out, addend, bias)
+
+    def call(stream=None, _keep=keep):
+        _check(lib.tpq_decode_reduce_fused(*args, _stream(stream)), "tpq_decode_reduce_fused")
+    return call
+
+
+def decode_reduce_fused(L, plan, msgs, out, addend=None, bias=None, accum: int = ACC_FP32, stream=None) -> None:
+    """out = ((sum of the dequantised msgs) + addend) + bias, in one kernel."""
+    decode_reduce_fused_call(L, plan, msgs, out, addend, bias, accum)(stream)
 
 
 # ---- static symmetric mode -------------------------------------------------------

@@ -278,6 +278,48 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
     return launch_decode(a, pc, ps, pz, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
 
+int tpq_decode_reduce_fused(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
+                            const uint8_t *const *codes, const uint16_t *const *scale,
+                            const uint16_t *const *zero, const uint16_t *const *outl,
+                            const uint16_t *addend, int64_t ldAdd, const uint16_t *bias, int accum,
+                            int out_dtype, void *out, int64_t ldOut, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the epilogue is built for 4-bit codes
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
+    if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
+    if (T > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
+    if (addend && ldAdd < L->E) return TPQ_ERR_SHAPE;
+    if ((ldOut % (out_dtype == TPQ_OUT_FP32 ? 4 : 8)) != 0) return TPQ_ERR_ALIGN;
+    if (!plan || !out) return TPQ_ERR_NULL;
+    if (!aligned16(plan) || !aligned16(out)) return TPQ_ERR_ALIGN;
+    // rows of the addend and the bias are read with 2-byte aligned loads
+    RankPtrs pc, ps, pz, po;
+    const bool quant = L->r > 0, keep = L->k > 0;
+    if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(ps, reinterpret_cast<const void *const *>(scale), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(pz, reinterpret_cast<const void *const *>(zero), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
+    if (T == 0) return TPQ_OK;
+    DecodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldOut = ldOut;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.out = out;
+    a.bits = 4;
+    a.addend = reinterpret_cast<const uint8_t *>(addend);
+    a.ldAdd = ldAdd;
+    a.bias = reinterpret_cast<const uint8_t *>(bias);
+    return launch_decode(a, pc, ps, pz, po, accum, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 // ---- static symmetric mode ----------------------------------------------------
 
 size_t tpq_static_table_floats(const tpq_layout *L)

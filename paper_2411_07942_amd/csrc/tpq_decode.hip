@@ -130,6 +130,87 @@ __device__ __forceinline__ void store_pass(u32x4 *st, const float (&acc)[8], uin
     __builtin_amdgcn_wave_barrier();
 }
 
+// one more term of the accumulation (fp32 add; rounded to bf16 in the literal bf16 chain)
+template <int ACC>
+__device__ __forceinline__ float add_term(float acc, float x)
+{
+    const float s = acc + x;
+    return ACC == TPQ_ACC_BF16 ? round_via_bf16(s) : s;
+}
+
+// ---------------------------------------------------------------------------
+// store_pass with the block's epilogue (Sec. 2: the sum over the devices plus the bias):
+// the sums are parked as fp32 whatever the output type, and every block adds the addend
+// row's and the bias's 8 columns (one 2-byte-aligned 128-bit load each) as two more terms
+// of the accumulation before it is rounded and stored.  addend_row / bias may be null.
+// st: 128 x 16 bytes per wave.
+// ---------------------------------------------------------------------------
+template <int OUT, int ACC>
+__device__ __forceinline__ void store_pass_fused(u32x4 *st, const float (&acc)[8], uint8_t *out_row,
+                                                 uint32_t lane, const uint32_t *entries, uint32_t nb,
+                                                 uint32_t nall, uint32_t e0, uint32_t e1,
+                                                 const uint8_t *addend_row, const uint8_t *bias)
+{
+    st[2u * lane] = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]),
+                          __float_as_uint(acc[3])};
+    st[2u * lane + 1u] = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]), __float_as_uint(acc[6]),
+                               __float_as_uint(acc[7])};
+    wave_lds_fence();
+    for (uint32_t s0 = 0; s0 < nall; s0 += 64) {
+        const uint32_t slot = s0 + lane;
+        uint32_t e = s0 == 0 ? e0 : e1;
+        if (s0 >= 128) e = slot < nall ? entries[slot] : 0u;
+        const uint32_t col = e & 0xFFFFu, at = (e >> 16) & 0x1FFu;
+        if (slot < nb) {
+            const uint32_t q = at >> 2;
+            const u32x4 A = st[q], B = st[min(q + 1u, 127u)], C = st[min(q + 2u, 127u)];
+            const bool s2 = (at & 2u) != 0, s1 = (at & 1u) != 0;
+#define TPQ_SEL(c, hi, lo) ((c) ? (hi) : (lo))
+            const uint32_t u0 = TPQ_SEL(s2, A.z, A.x), u1 = TPQ_SEL(s2, A.w, A.y), u2 = TPQ_SEL(s2, B.x, A.z),
+                           u3 = TPQ_SEL(s2, B.y, A.w), u4 = TPQ_SEL(s2, B.z, B.x), u5 = TPQ_SEL(s2, B.w, B.y),
+                           u6 = TPQ_SEL(s2, C.x, B.z), u7 = TPQ_SEL(s2, C.y, B.w), u8 = TPQ_SEL(s2, C.z, C.x);
+            float f0 = __uint_as_float(TPQ_SEL(s1, u1, u0)), f1 = __uint_as_float(TPQ_SEL(s1, u2, u1)),
+                  f2 = __uint_as_float(TPQ_SEL(s1, u3, u2)), f3 = __uint_as_float(TPQ_SEL(s1, u4, u3)),
+                  f4 = __uint_as_float(TPQ_SEL(s1, u5, u4)), f5 = __uint_as_float(TPQ_SEL(s1, u6, u5)),
+                  f6 = __uint_as_float(TPQ_SEL(s1, u7, u6)), f7 = __uint_as_float(TPQ_SEL(s1, u8, u7));
+#undef TPQ_SEL
+#define TPQ_ADD8(src)                                                                       \
+    {                                                                                       \
+        const u32x4 t8 = *reinterpret_cast<const u32x4_a2 *>((src) + 2u * col);             \
+        f0 = add_term<ACC>(f0, bf16_lo_to_f32(t8.x)); f1 = add_term<ACC>(f1, bf16_hi_to_f32(t8.x)); \
+        f2 = add_term<ACC>(f2, bf16_lo_to_f32(t8.y)); f3 = add_term<ACC>(f3, bf16_hi_to_f32(t8.y)); \
+        f4 = add_term<ACC>(f4, bf16_lo_to_f32(t8.z)); f5 = add_term<ACC>(f5, bf16_hi_to_f32(t8.z)); \
+        f6 = add_term<ACC>(f6, bf16_lo_to_f32(t8.w)); f7 = add_term<ACC>(f7, bf16_hi_to_f32(t8.w)); \
+    }
+            if (addend_row) TPQ_ADD8(addend_row)
+            if (bias) TPQ_ADD8(bias)
+#undef TPQ_ADD8
+            if (OUT == TPQ_OUT_FP32) {
+                __builtin_nontemporal_store(
+                    u32x4{__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3)},
+                    reinterpret_cast<u32x4_a4 *>(out_row + 4u * col));
+                __builtin_nontemporal_store(
+                    u32x4{__float_as_uint(f4), __float_as_uint(f5), __float_as_uint(f6), __float_as_uint(f7)},
+                    reinterpret_cast<u32x4_a4 *>(out_row + 4u * col + 16u));
+            } else {
+                __builtin_nontemporal_store(u32x4{pack_bf16x2(f0, f1), pack_bf16x2(f2, f3), pack_bf16x2(f4, f5),
+                                                  pack_bf16x2(f6, f7)},
+                                            reinterpret_cast<u32x4_a2 *>(out_row + 2u * col));
+            }
+        } else if (slot < nall) {
+            float f = __uint_as_float(reinterpret_cast<const uint32_t *>(st)[at]);
+            if (addend_row)
+                f = add_term<ACC>(f, bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(addend_row + 2u * col)));
+            if (bias) f = add_term<ACC>(f, bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(bias + 2u * col)));
+            if (OUT == TPQ_OUT_FP32)
+                *reinterpret_cast<float *>(out_row + 4u * col) = f;
+            else
+                *reinterpret_cast<uint16_t *>(out_row + 2u * col) = static_cast<uint16_t>(pack_bf16x2(f, f));
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ---------------------------------------------------------------------------
 // One wavefront handles one pass (64 chunks = 512 compacted features) of one output
 // row, or up to 64 of the row's selected features; waves are independent (no barrier;
@@ -151,7 +232,9 @@ __device__ __forceinline__ void store_pass(u32x4 *st, const float (&acc)[8], uin
 // GEN selects code widths other than 4 bits (Sec. 4, the experiment that varies the bits
 // of the quantised features): a chunk's 8 codes are b bytes at byte chunk * b of the row,
 // fetched with one 64-bit load at that byte (the row's pitch leaves room behind the last).
-template <int LPG, int ACC, int OUT, bool GEN>
+//
+// FUSED adds the block's epilogue (an addend row and / or the bias, see store_pass_fused).
+template <int LPG, int ACC, int OUT, bool GEN, bool FUSED>
 __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs codesp, RankPtrs scalep,
                                                      RankPtrs zerop, RankPtrs outlp)
 {
@@ -194,6 +277,12 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
                     }
                 }
             }
+        }
+        if constexpr (FUSED) {
+            if (a.addend)
+                acc = add_term<ACC>(acc, bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(
+                                             a.addend + static_cast<int64_t>(t) * a.ldAdd * 2)[j]));
+            if (a.bias) acc = add_term<ACC>(acc, bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(a.bias)[j]));
         }
         if (OUT == TPQ_OUT_FP32)
             *reinterpret_cast<float *>(out_row + 4u * j) = acc;
@@ -275,9 +364,15 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     uint32_t i0 = 0;
     for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
     if (i0 < N) batch(i0, std::false_type{});
-    __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
-    store_pass<OUT>(stage + wave * (64u * (OUT == TPQ_OUT_FP32 ? 2u : 1u)), acc, out_row, lane, entries, nb,
-                    nall, e0, e1);
+    if constexpr (FUSED) {
+        __shared__ u32x4 stage_f[4 * 128];
+        store_pass_fused<OUT, ACC>(stage_f + wave * 128u, acc, out_row, lane, entries, nb, nall, e0, e1,
+                                   a.addend ? a.addend + static_cast<int64_t>(t) * a.ldAdd * 2 : nullptr, a.bias);
+    } else {
+        __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
+        store_pass<OUT>(stage + wave * (64u * (OUT == TPQ_OUT_FP32 ? 2u : 1u)), acc, out_row, lane, entries,
+                        nb, nall, e0, e1);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -443,10 +538,12 @@ static void launch_rows(int rpw, dim3 grid, hipStream_t s, const DecodeArgs &a, 
         else
             k_decode_static<ACC, OUT, 1><<<grid, 256, 0, s>>>(a, codes, outl);
     } else {
-        if (a.bits != 4)
-            k_decode_pass<LPG, ACC, OUT, true><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+        if (a.addend || a.bias)  // (4 bits only: the host refuses the epilogue at other widths)
+            k_decode_pass<LPG, ACC, OUT, false, true><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+        else if (a.bits != 4)
+            k_decode_pass<LPG, ACC, OUT, true, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
         else
-            k_decode_pass<LPG, ACC, OUT, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+            k_decode_pass<LPG, ACC, OUT, false, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
     }
 }
 
@@ -478,6 +575,7 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
         RankPtrs codes = codes_in, scale = scale_in, zero = zero_in, outl = outl_in;
         a.T = a_in.T - row0 < rows_per_launch ? a_in.T - row0 : rows_per_launch;
         a.out = static_cast<uint8_t *>(a_in.out) + row0 * a_in.ldOut * ob;
+        if (a_in.addend) a.addend = a_in.addend + row0 * a_in.ldAdd * 2;
         for (int i = 0; i < a_in.n_ranks; ++i) {
             if (codes.p[i]) codes.p[i] = static_cast<const uint8_t *>(codes.p[i]) + row0 * a_in.pitch_codes;
             if (scale.p[i]) scale.p[i] = static_cast<const uint8_t *>(scale.p[i]) + row0 * a_in.pitch_meta;

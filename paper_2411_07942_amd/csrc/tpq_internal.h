@@ -221,6 +221,10 @@ struct DecodeArgs {
     int64_t pitch_codes, pitch_meta, pitch_outl;
     void *out;
     int32_t bits;  // code width
+    // epilogue (either may be null): addend bf16 [T][ldAdd], bias bf16 [E]
+    const uint8_t *addend;
+    int64_t ldAdd;
+    const uint8_t *bias;
     // static symmetric mode: steps, fp32 [n_ranks][static_stride] in compacted order
     const float *step_c;
     int32_t static_stride;
