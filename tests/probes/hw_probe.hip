@@ -9,6 +9,10 @@
 //   5. hardware reciprocal + one Newton step == 1 / s (IEEE) for EVERY bf16 value s whose
 //      reciprocal is a normal number and that the encoder can meet (1e-30 <= s <= 4.6e37).
 //   6. v_perm_b32 byte order as used to collect the packed codes.
+//   7. static mode: clamp to [-8, 7], add 1.5 * 2^23 + 8: the sum's low byte is rint(.) + 8.
+//   8. one value rounded to bf16 by the pair conversion with a zero in the low half.
+//   9. v_cvt_pk_u8_f32 saturates at 255 (the clamp of the 8-bit code width).
+//  10. 2-, 4- and 8-byte global accesses at any byte address (code widths other than 4 bits).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
@@ -55,6 +59,46 @@ __global__ void k_recip(unsigned *fast, unsigned *ieee)
     const float e = __builtin_fmaf(-s, y, 1.0f);
     fast[h] = __float_as_uint(__builtin_fmaf(e, y, y));
     ieee[h] = __float_as_uint(1.0f / s);
+}
+
+// static mode: clamp, then add 1.5 * 2^23 + 8: the low byte is rint(.) + 8
+__global__ void k_magic(const float *p, unsigned *out, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float c = __builtin_amdgcn_fmed3f(p[i], -8.0f, 7.0f);
+    out[i] = __float_as_uint(c + 12582920.0f) & 0xFFu;
+}
+
+// 8-bit codes: the float -> byte conversion saturates at 255
+__global__ void k_sat(const float *p, unsigned *out, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    out[i] = __builtin_amdgcn_cvt_pk_u8_f32(p[i], 0u, 0u);
+}
+
+// byte-aligned 2-, 4- and 8-byte accesses (code widths other than 4 bits)
+typedef unsigned short u16_a1 __attribute__((aligned(1)));
+typedef unsigned int u32_a1 __attribute__((aligned(1)));
+typedef unsigned long long u64_a1 __attribute__((aligned(1)));
+__global__ void k_unaligned(unsigned char *buf, unsigned long long *loaded)
+{
+    const unsigned l = threadIdx.x;  // 64 lanes, 16 bytes apart, offsets l % 8
+    unsigned char *p = buf + 16u * l + (l & 7u);
+    loaded[l] = *reinterpret_cast<const u64_a1 *>(p);
+    unsigned char *q = buf + 2048u + 16u * l + (l & 7u);
+    *reinterpret_cast<u16_a1 *>(q) = static_cast<unsigned short>(0xB1A0u + l);
+    *reinterpret_cast<u32_a1 *>(q + 2) = 0xC0DE0000u + l;
+}
+
+// one value rounded to bf16 by the pair conversion with a zero low half
+__global__ void k_round1(const float *f, unsigned *out, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const f32x2 v = {0.0f, f[i]};
+    out[i] = __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
 
 __global__ void k_perm(unsigned *out)
@@ -156,6 +200,72 @@ int main()
         CK(hipMemcpy(&h, d, 4, hipMemcpyDeviceToHost));
         printf("v_perm_b32 selector   : %s (0x%08x)\n", h == 0x88664422u ? "ok" : "FAIL", h);
         fails += h != 0x88664422u;
+    }
+    {   // 7, 8, 9: static-mode rounding, saturation, single-value bf16 rounding
+        const int n = 1 << 18;
+        float *hf = (float *)malloc(n * 4);
+        for (int i = 0; i < n; ++i) hf[i] = -10.0f + 20.0f * (float)i / (float)n;
+        for (int k = -9; k < 9; ++k) {
+            hf[3 * (k + 9)] = k + 0.5f;
+            hf[3 * (k + 9) + 1] = nextafterf(k + 0.5f, 100.f);
+            hf[3 * (k + 9) + 2] = nextafterf(k + 0.5f, -100.f);
+        }
+        float *df; unsigned *d;
+        CK(hipMalloc(&df, n * 4)); CK(hipMalloc(&d, n * 4));
+        CK(hipMemcpy(df, hf, n * 4, hipMemcpyHostToDevice));
+        unsigned *h = (unsigned *)malloc(n * 4);
+        k_magic<<<n / 256, 256>>>(df, d, n);
+        CK(hipMemcpy(h, d, n * 4, hipMemcpyDeviceToHost));
+        long bad = 0;
+        for (int i = 0; i < n; ++i) {
+            float q = rintf(hf[i]);
+            q = q < -8.f ? -8.f : (q > 7.f ? 7.f : q);
+            bad += h[i] != (unsigned)((int)q + 8);
+        }
+        printf("clamp + magic rounding: %s (%ld of %d differ)\n", bad ? "FAIL" : "ok", bad, n);
+        fails += bad != 0;
+        k_round1<<<n / 256, 256>>>(df, d, n);
+        CK(hipMemcpy(h, d, n * 4, hipMemcpyDeviceToHost));
+        bad = 0;
+        for (int i = 0; i < n; ++i) bad += h[i] != (bf16_rne(hf[i]) << 16);
+        printf("bf16 rounding, 1 value: %s (%ld of %d differ)\n", bad ? "FAIL" : "ok", bad, n);
+        fails += bad != 0;
+        for (int i = 0; i < n; ++i) hf[i] = 240.0f + 80.0f * (float)i / (float)n;
+        CK(hipMemcpy(df, hf, n * 4, hipMemcpyHostToDevice));
+        k_sat<<<n / 256, 256>>>(df, d, n);
+        CK(hipMemcpy(h, d, n * 4, hipMemcpyDeviceToHost));
+        bad = 0;
+        for (int i = 0; i < n; ++i) {
+            const float q = rintf(hf[i]);
+            bad += h[i] != (unsigned)(q > 255.f ? 255.f : q);
+        }
+        printf("cvt_pk_u8 saturation  : %s (%ld of %d differ)\n", bad ? "FAIL" : "ok", bad, n);
+        fails += bad != 0;
+    }
+    {   // 10: byte-aligned accesses
+        unsigned char hb[4096], *db;
+        for (int i = 0; i < 4096; ++i) hb[i] = (unsigned char)(i * 7 + 3);
+        unsigned long long *dl, hl[64];
+        CK(hipMalloc(&db, 4096)); CK(hipMalloc(&dl, 64 * 8));
+        CK(hipMemcpy(db, hb, 4096, hipMemcpyHostToDevice));
+        k_unaligned<<<1, 64>>>(db, dl);
+        unsigned char after[4096];
+        CK(hipMemcpy(after, db, 4096, hipMemcpyDeviceToHost));
+        CK(hipMemcpy(hl, dl, 64 * 8, hipMemcpyDeviceToHost));
+        long bad = 0;
+        for (unsigned l = 0; l < 64; ++l) {
+            unsigned long long want;
+            memcpy(&want, hb + 16 * l + (l & 7), 8);
+            bad += hl[l] != want;
+            unsigned char *q = hb + 2048 + 16 * l + (l & 7);
+            const unsigned short a = (unsigned short)(0xB1A0u + l);
+            const unsigned b = 0xC0DE0000u + l;
+            memcpy(q, &a, 2);
+            memcpy(q + 2, &b, 4);
+        }
+        bad += memcmp(hb, after, 4096) != 0;
+        printf("byte-aligned accesses : %s\n", bad ? "FAIL" : "ok");
+        fails += bad != 0;
     }
     printf("%s\n", fails ? "HW PROBE FAILED" : "HW PROBE OK");
     return fails ? 1 : 0;

@@ -382,3 +382,46 @@ def test_calibration_config_reduced_stream_and_resume():
         tpq.calibrate(Y, 0, N, s, 0.01, mC, MC, ws)
     torch.cuda.synchronize()
     assert torch.equal(mA, mC) and torch.equal(MA, MC)
+
+
+def test_hip_graph_replays_match_eager():
+    """encode + decode_reduce of several blocks captured in one HIP graph: every replay, with
+    eager work and synchronisation in between, gives the eager result."""
+    w = wl.TINY
+    L = tpq.layout_init(w.E, w.k, w.G)
+    plan = gpu_plan(L, idx_for(w))
+    blocks = []
+    for b in range(3):
+        Ys = wl.partial_sums(w, block=b, device="cuda")
+        msgs = [tpq.Message(L, w.T, "cuda") for _ in range(w.N)]
+        out = torch.empty((w.T, w.E), dtype=torch.bfloat16, device="cuda")
+        bias = torch.linspace(-1, 1, w.E, device="cuda").to(torch.bfloat16)
+        blocks.append(dict(enc=tpq.encode_call(L, plan, Ys, msgs),
+                           dec=tpq.decode_reduce_fused_call(L, plan, msgs, out, None, bias, tpq.ACC_BF16),
+                           out=out, msgs=msgs, keep=(Ys, bias)))
+    calls = [c for blk in blocks for c in (blk["enc"], blk["dec"])]
+    for c in calls:
+        c()
+    torch.cuda.synchronize()
+    eager = [blk["out"].clone() for blk in blocks]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for c in calls:
+            c()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for c in calls:
+            c()
+    for rep in range(4):
+        for blk in blocks:                      # eager work between the replays
+            blk["out"].fill_(3.0)
+            for m in blk["msgs"]:
+                m.codes.fill_(0x5A)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for blk, e in zip(blocks, eager):
+            assert torch.equal(blk["out"], e), "replay %d differs from the eager result" % rep
