@@ -62,6 +62,10 @@ def _load():
         lib.orc_decode_reduce_bits.argtypes = [i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
                                                i32, i32, vp, i32]
         lib.orc_static_params.argtypes = [vp, vp, i32, i32, vp, vp]
+        lib.orc_static_params_bits.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        lib.orc_encode_static_bits.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, i32]
+        lib.orc_decode_reduce_static_bits.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, i32, i32,
+                                                      vp, i32]
         lib.orc_encode_static.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce_static.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp, i32, i32,
                                                  vp, i32]
@@ -252,19 +256,24 @@ class StaticMessage:
     codes: np.ndarray  # uint8  [T,cb]  nibble = code + 8, two per byte, low nibble first
 
 
-def static_params(m, M):
+def static_params(m, M, bits: int = 4, generic: bool = False):
     """(step, inv) fp32 [N,E] from the calibrated (m, M) fp32 [N,E]."""
     m = np.ascontiguousarray(m, dtype=np.float32)
     M = np.ascontiguousarray(M, dtype=np.float32)
     N, E = m.shape
     step = np.empty((N, E), np.float32)
     inv = np.empty((N, E), np.float32)
-    if _load().orc_static_params(_ptr(m), _ptr(M), N, E, _ptr(step), _ptr(inv)):
+    if bits == 4 and not generic:
+        rc = _load().orc_static_params(_ptr(m), _ptr(M), N, E, _ptr(step), _ptr(inv))
+    else:
+        rc = _load().orc_static_params_bits(_ptr(m), _ptr(M), N, E, bits, _ptr(step), _ptr(inv))
+    if rc:
         raise ValueError("orc_static_params: bad arguments")
     return step, inv
 
 
-def encode_static(Y, idx_sorted, inv_row, threads: int = 1) -> StaticMessage:
+def encode_static(Y, idx_sorted, inv_row, threads: int = 1, bits: int = 4,
+                  generic: bool = False) -> StaticMessage:
     """Y: one device's bf16 bits [T,E]; inv_row: that device's fp32 [E]."""
     Y = _u16(Y)
     T, E = Y.shape
@@ -272,17 +281,21 @@ def encode_static(Y, idx_sorted, inv_row, threads: int = 1) -> StaticMessage:
     inv_row = np.ascontiguousarray(inv_row, dtype=np.float32)
     assert inv_row.shape == (E,)
     k = idx_sorted.shape[0]
-    cb = (E - k + 1) // 2
+    cb = ((E - k) * bits + 7) // 8
     msg = StaticMessage(np.empty((T, k), np.uint16), np.empty((T, cb), np.uint8))
-    rc = _load().orc_encode_static(_ptr(Y), T, E, E, k, _ptr(idx_sorted), _ptr(inv_row),
-                                   _ptr(msg.outl), _ptr(msg.codes), threads)
+    if bits == 4 and not generic:
+        rc = _load().orc_encode_static(_ptr(Y), T, E, E, k, _ptr(idx_sorted), _ptr(inv_row),
+                                       _ptr(msg.outl), _ptr(msg.codes), threads)
+    else:
+        rc = _load().orc_encode_static_bits(_ptr(Y), T, E, E, k, bits, _ptr(idx_sorted), _ptr(inv_row),
+                                            _ptr(msg.outl), _ptr(msg.codes), threads)
     if rc:
         raise ValueError("orc_encode_static: bad arguments")
     return msg
 
 
 def decode_reduce_static(msgs, idx_sorted, step, accum: int = ACC_FP32, out_fp32: bool = False,
-                         threads: int = 1) -> np.ndarray:
+                         threads: int = 1, bits: int = 4, generic: bool = False) -> np.ndarray:
     """step: fp32 [N,E].  Dequantise the N static-mode messages and add them."""
     N = len(msgs)
     step = np.ascontiguousarray(step, dtype=np.float32)
@@ -291,7 +304,7 @@ def decode_reduce_static(msgs, idx_sorted, step, accum: int = ACC_FP32, out_fp32
     idx_sorted = np.ascontiguousarray(idx_sorted, dtype=np.int32)
     k = idx_sorted.shape[0]
     T = msgs[0].codes.shape[0] if k < E else msgs[0].outl.shape[0]
-    cb = (E - k + 1) // 2
+    cb = ((E - k) * bits + 7) // 8
     keep = []
 
     def table(name, dtype, shape):
@@ -306,8 +319,13 @@ def decode_reduce_static(msgs, idx_sorted, step, accum: int = ACC_FP32, out_fp32
     codes = table("codes", np.uint8, (T, cb))
     outl = table("outl", np.uint16, (T, k))
     out = np.empty((T, E), np.float32 if out_fp32 else np.uint16)
-    rc = _load().orc_decode_reduce_static(N, T, E, k, _ptr(idx_sorted), codes, outl, _ptr(step),
-                                          accum, int(bool(out_fp32)), _ptr(out), threads)
+    if bits == 4 and not generic:
+        rc = _load().orc_decode_reduce_static(N, T, E, k, _ptr(idx_sorted), codes, outl, _ptr(step),
+                                              accum, int(bool(out_fp32)), _ptr(out), threads)
+    else:
+        rc = _load().orc_decode_reduce_static_bits(N, T, E, k, bits, _ptr(idx_sorted), codes, outl,
+                                                   _ptr(step), accum, int(bool(out_fp32)), _ptr(out),
+                                                   threads)
     if rc:
         raise ValueError("orc_decode_reduce_static: bad arguments")
     return out

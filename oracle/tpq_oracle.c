@@ -626,6 +626,119 @@ int orc_decode_reduce_bits(int N, int64_t T, int E, int k, int G, int bits,
     return ORC_OK;
 }
 
+/* ---- static symmetric mode at other bit widths --------------------------- */
+
+/*
+ * The static symmetric quantiser with b-bit codes (Sec. 4, Fig. 3 varies the bits of the
+ * paper's own quantiser): step = R / (2^b - 1), code = rint(x * (1/step)) clamped to
+ * -2^(b-1) .. 2^(b-1) - 1, travelling as the field code + 2^(b-1) of the row's bit string.
+ * b = 4 gives orc_static_params / orc_encode_static / orc_decode_reduce_static.
+ */
+int orc_static_params_bits(const float *m, const float *M, int N, int E, int bits, float *step,
+                           float *inv)
+{
+    if (!m || !M || !step || !inv || N < 1 || E < 1 || !bits_ok(bits)) return ORC_ERR_ARG;
+    float qmax = (float)((1 << bits) - 1);
+    for (int64_t q = 0; q < (int64_t)N * E; ++q) {
+        float lo = -m[q], hi = M[q];
+        float R = 2.0f * (lo > hi ? lo : hi);
+        R += 0.0f;
+        float d = R / qmax;
+        if (!(d >= 1e-30f)) {
+            step[q] = 0.0f;
+            inv[q] = 0.0f;
+        } else {
+            step[q] = d;
+            inv[q] = 1.0f / d;
+        }
+    }
+    return ORC_OK;
+}
+
+int orc_encode_static_bits(const uint16_t *Y, int64_t T, int64_t ldY, int E, int k, int bits,
+                           const int32_t *idx_sorted, const float *inv, uint16_t *outl,
+                           uint8_t *codes, int threads)
+{
+    if (!Y || T < 0 || E < 1 || k < 0 || k > E || ldY < E || !bits_ok(bits)) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !inv)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int64_t cb = ((int64_t)r * bits + 7) / 8;
+    float half = (float)(1 << (bits - 1));
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const uint16_t *y = Y + t * ldY;
+        for (int p = 0; p < k; ++p) outl[t * k + p] = y[idx_sorted[p]];
+        uint8_t *row = codes ? codes + t * cb : NULL;
+        if (row) memset(row, 0, (size_t)cb);
+        for (int c = 0; c < r; ++c) {
+            int j = comp[c];
+            float x = bf16_to_f32(y[j]);
+            float p = x * inv[j];
+            float q = rintf(p); /* ties to even */
+            if (q < -half) q = -half;
+            if (q > half - 1.0f) q = half - 1.0f;
+            put_code(row, c, bits, (unsigned)((int)q + (int)half));
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
+int orc_decode_reduce_static_bits(int N, int64_t T, int E, int k, int bits,
+                                  const int32_t *idx_sorted, const uint8_t *const *codes,
+                                  const uint16_t *const *outl, const float *step, int accum,
+                                  int out_fp32, void *out, int threads)
+{
+    if (N < 1 || T < 0 || E < 1 || k < 0 || k > E || !out || !bits_ok(bits)) return ORC_ERR_ARG;
+    if (accum != ORC_ACC_FP32 && accum != ORC_ACC_BF16) return ORC_ERR_ARG;
+    if (k > 0 && (!idx_sorted || !outl)) return ORC_ERR_ARG;
+    if (k < E && (!codes || !step)) return ORC_ERR_ARG;
+    if (!check_indices(idx_sorted, k, E)) return ORC_ERR_ARG;
+    int r = E - k;
+    int64_t cb = ((int64_t)r * bits + 7) / 8;
+    int half = 1 << (bits - 1);
+    int32_t *comp = build_compaction(idx_sorted, k, E);
+    if (!comp) return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float *of = out_fp32 ? (float *)out + t * E : NULL;
+        uint16_t *ob = out_fp32 ? NULL : (uint16_t *)out + t * E;
+        for (int col = 0; col < E; ++col) {
+            int is_outlier = col >= r;
+            int j = is_outlier ? idx_sorted[col - r] : comp[col];
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                float x;
+                if (is_outlier) {
+                    x = bf16_to_f32(outl[i][t * k + (col - r)]);
+                } else {
+                    int field = (int)get_code(codes[i] + t * cb, col, bits);
+                    float q = (float)(field - half);
+                    x = q * step[(int64_t)i * E + j];
+                }
+                if (accum == ORC_ACC_BF16) {
+                    x = round_to_bf16(x);
+                    acc = (i == 0) ? x : round_to_bf16(acc + x);
+                } else {
+                    acc = (i == 0) ? x : acc + x;
+                }
+            }
+            if (of)
+                of[j] = acc;
+            else
+                ob[j] = f32_to_bf16(acc);
+        }
+    }
+    free(comp);
+    return ORC_OK;
+}
+
 /* ---- static symmetric mode --------------------------------------------- */
 
 /*
