@@ -210,8 +210,9 @@ int tpq_decode_reduce_fused(const tpq_layout *L, const void *plan, int n_ranks, 
  * x * (1/step) clamped to -8..7, x_hat = code * step.  A feature whose
  * calibrated range vanishes (step < 1e-30) is sent as code 0 and comes back as 0.
  * The message is the codes section (same layout; the nibble is code + 8) and the
- * outl section: nothing else travels, 4 + 12k/E bits per value.  This mode is built
- * for 4-bit codes: a layout of another width is refused (TPQ_ERR_UNSUPPORTED).
+ * outl section: nothing else travels, 4 + 12k/E bits per value.  For a layout of
+ * another width b (Sec. 4, Fig. 3): step = R/(2^b - 1), codes -2^(b-1) .. 2^(b-1) - 1,
+ * sent as the field code + 2^(b-1) of the row's bit string; b + (16-b)k/E bits.
  *
  * tpq_static_params turns the calibration state into the two tables the kernels
  * read, in the compacted feature order of `plan`:

@@ -333,7 +333,6 @@ int tpq_static_params(const tpq_layout *L, const void *plan, const float *m, con
 {
     int rc = check_layout(L);
     if (rc) return rc;
-    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS) return TPQ_ERR_SHAPE;
     if (L->r == 0) return TPQ_OK;
     if (!plan || !m || !M || !step || !inv) return TPQ_ERR_NULL;
@@ -347,7 +346,6 @@ int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *con
 {
     int rc = check_layout(L);
     if (rc) return rc;
-    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldY < L->E) return TPQ_ERR_SHAPE;
     if (T * n_ranks > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
     if ((ldY % 8) != 0) return TPQ_ERR_ALIGN;
@@ -373,8 +371,8 @@ int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *con
     a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
     a.inv_c = inv;
     a.static_stride = 8 * a.chunks_padded;
-    a.bits = 4;
-    a.qmax = 15.0f;
+    a.bits = L->bits;
+    a.qmax = static_cast<float>((1 << L->bits) - 1);
     return launch_encode(a, pY, pc, none, none, po, static_cast<hipStream_t>(stream));
 }
 
@@ -385,7 +383,6 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
 {
     int rc = check_layout(L);
     if (rc) return rc;
-    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the static mode is built for 4 bits
     if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
     if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
@@ -413,7 +410,7 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
     a.out = out;
     a.step_c = quant ? step : nullptr;
     a.static_stride = 8 * a.chunks_padded;
-    a.bits = 4;
+    a.bits = L->bits;
     return launch_decode(a, pc, none, none, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
 

@@ -384,7 +384,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
 // loads two to one.  Rows past the end are read as the last row and not stored.
 // grid: x = block of R rows, y = groups of 4 waves.
 // ---------------------------------------------------------------------------
-template <int ACC, int OUT, int R>
+template <int ACC, int OUT, int R, bool GEN>
 __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs codesp, RankPtrs outlp)
 {
     if (plan_header_bad(a.plan, a.E, a.k, a.G)) return;
@@ -466,13 +466,15 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     uint32_t off_codes[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr)
-        off_codes[rr] = tr[rr] * static_cast<uint32_t>(a.pitch_codes) + 4u * min(chunk, chunks - 1u);
+        off_codes[rr] = tr[rr] * static_cast<uint32_t>(a.pitch_codes) +
+                        (GEN ? static_cast<uint32_t>(a.bits) : 4u) * min(chunk, chunks - 1u);
     float acc[R][8];
 
     // static mode, 4 ranks at a time: a code word per row and 8 steps each
     auto batch_static = [&](uint32_t i0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         uint32_t w[R][4];
+        uint64_t wq[R][4];  // GEN
         float4 sa[4], sb[4];
         const void *const *pc = codesp.p + i0;
         const float *tab = a.step_c + 8u * chunk;  // chunk < chunks_padded: inside the row
@@ -481,8 +483,12 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
             const uint32_t i = FULL ? static_cast<uint32_t>(j) : min(static_cast<uint32_t>(j), N - 1u - i0);
 #pragma unroll
             for (int rr = 0; rr < R; ++rr)
-                w[rr][j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
-                    static_cast<const uint8_t *>(pc[i]) + off_codes[rr]));
+                if constexpr (GEN)
+                    wq[rr][j] = __builtin_nontemporal_load(reinterpret_cast<const u64_a1 *>(
+                        static_cast<const uint8_t *>(pc[i]) + off_codes[rr]));
+                else
+                    w[rr][j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                        static_cast<const uint8_t *>(pc[i]) + off_codes[rr]));
             const float *row = tab + static_cast<int64_t>(i0 + i) * a.static_stride;
             sa[j] = *reinterpret_cast<const float4 *>(row);
             sb[j] = *reinterpret_cast<const float4 *>(row + 4);
@@ -493,13 +499,27 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
                 const float st[8] = {sa[j].x, sa[j].y, sa[j].z, sa[j].w, sb[j].x, sb[j].y, sb[j].z, sb[j].w};
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
-                    uint32_t lo = w[rr][j] & 0x0F0F0F0Fu, hi = (w[rr][j] >> 4) & 0x0F0F0F0Fu;
-                    asm volatile("" : "+v"(lo), "+v"(hi));
                     float x[8];
+                    if constexpr (GEN) {
+                        float c[8];
+                        switch (a.bits) {
+                        case 2: unpack_codes<2>(wq[rr][j], c); break;
+                        case 3: unpack_codes<3>(wq[rr][j], c); break;
+                        case 5: unpack_codes<5>(wq[rr][j], c); break;
+                        case 6: unpack_codes<6>(wq[rr][j], c); break;
+                        default: unpack_codes<8>(wq[rr][j], c); break;
+                        }
+                        const float half = static_cast<float>(1u << (static_cast<uint32_t>(a.bits) - 1u));
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
-                        x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
+                        for (int e = 0; e < 8; ++e) x[e] = (c[e] - half) * st[e];
+                    } else {
+                        uint32_t lo = w[rr][j] & 0x0F0F0F0Fu, hi = (w[rr][j] >> 4) & 0x0F0F0F0Fu;
+                        asm volatile("" : "+v"(lo), "+v"(hi));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
+                            x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
+                        }
                     }
                     accumulate8<ACC>(acc[rr], x, i0 + j == 0);
                 }
@@ -533,10 +553,16 @@ static void launch_rows(int rpw, dim3 grid, hipStream_t s, const DecodeArgs &a, 
                         const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl)
 {
     if constexpr (LPG == 0) {
-        if (rpw == 4)
-            k_decode_static<ACC, OUT, 4><<<grid, 256, 0, s>>>(a, codes, outl);
-        else
-            k_decode_static<ACC, OUT, 1><<<grid, 256, 0, s>>>(a, codes, outl);
+        if (a.bits != 4) {
+            if (rpw == 4)
+                k_decode_static<ACC, OUT, 4, true><<<grid, 256, 0, s>>>(a, codes, outl);
+            else
+                k_decode_static<ACC, OUT, 1, true><<<grid, 256, 0, s>>>(a, codes, outl);
+        } else if (rpw == 4) {
+            k_decode_static<ACC, OUT, 4, false><<<grid, 256, 0, s>>>(a, codes, outl);
+        } else {
+            k_decode_static<ACC, OUT, 1, false><<<grid, 256, 0, s>>>(a, codes, outl);
+        }
     } else {
         if (a.addend || a.bias)  // (4 bits only: the host refuses the epilogue at other widths)
             k_decode_pass<LPG, ACC, OUT, false, true><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);

@@ -279,19 +279,45 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
             const float4 ib = *reinterpret_cast<const float4 *>(invr + 8u * chunk + 4u);
             const float iv[8] = {ia.x, ia.y, ia.z, ia.w, ib.x, ib.y, ib.z, ib.w};
             const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
-            uint32_t by[4];
+            if constexpr (GEN) {
+                // b-bit codes: clamp to -2^(b-1) .. 2^(b-1) - 1, then the same rounding by
+                // addition with 2^(b-1) (even for every b >= 2) in place of 8: the sum's low
+                // byte is the field code + 2^(b-1)
+                const float half = static_cast<float>(1u << (static_cast<uint32_t>(a.bits) - 1u));
+                const float magic = 12582912.0f + half;
+                uint32_t n[8];
 #pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float x0 = bf16_lo_to_f32(wv[e2]), x1 = bf16_hi_to_f32(wv[e2]);
-                const float c0 = __builtin_amdgcn_fmed3f(x0 * iv[2 * e2], -8.0f, 7.0f);
-                const float c1 = __builtin_amdgcn_fmed3f(x1 * iv[2 * e2 + 1], -8.0f, 7.0f);
-                const uint32_t n0 = __float_as_uint(c0 + 12582920.0f);
-                const uint32_t n1 = __float_as_uint(c1 + 12582920.0f);
-                by[e2] = (n1 << 4) | n0;  // low byte: the pair's two nibbles
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float x0 = bf16_lo_to_f32(wv[e2]), x1 = bf16_hi_to_f32(wv[e2]);
+                    const float c0 = __builtin_amdgcn_fmed3f(x0 * iv[2 * e2], -half, half - 1.0f);
+                    const float c1 = __builtin_amdgcn_fmed3f(x1 * iv[2 * e2 + 1], -half, half - 1.0f);
+                    n[2 * e2] = __float_as_uint(c0 + magic) & 0xFFu;
+                    n[2 * e2 + 1] = __float_as_uint(c1 + magic) & 0xFFu;
+                }
+                const uint32_t lo = n[0] | (n[1] << 8) | (n[2] << 16) | (n[3] << 24);
+                const uint32_t hi = n[4] | (n[5] << 8) | (n[6] << 16) | (n[7] << 24);
+                switch (a.bits) {
+                case 2: w64[p] = pack_codes<2>(lo, hi); break;
+                case 3: w64[p] = pack_codes<3>(lo, hi); break;
+                case 5: w64[p] = pack_codes<5>(lo, hi); break;
+                case 6: w64[p] = pack_codes<6>(lo, hi); break;
+                default: w64[p] = pack_codes<8>(lo, hi); break;
+                }
+            } else {
+                uint32_t by[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float x0 = bf16_lo_to_f32(wv[e2]), x1 = bf16_hi_to_f32(wv[e2]);
+                    const float c0 = __builtin_amdgcn_fmed3f(x0 * iv[2 * e2], -8.0f, 7.0f);
+                    const float c1 = __builtin_amdgcn_fmed3f(x1 * iv[2 * e2 + 1], -8.0f, 7.0f);
+                    const uint32_t n0 = __float_as_uint(c0 + 12582920.0f);
+                    const uint32_t n1 = __float_as_uint(c1 + 12582920.0f);
+                    by[e2] = (n1 << 4) | n0;  // low byte: the pair's two nibbles
+                }
+                const uint32_t lo = __builtin_amdgcn_perm(by[1], by[0], 0x00000400u);
+                const uint32_t hi = __builtin_amdgcn_perm(by[3], by[2], 0x00000400u);
+                w[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             }
-            const uint32_t lo = __builtin_amdgcn_perm(by[1], by[0], 0x00000400u);
-            const uint32_t hi = __builtin_amdgcn_perm(by[3], by[2], 0x00000400u);
-            w[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
     } else {
         // D: group min / max.  The upper feature of a word is compared as the whole
@@ -514,7 +540,7 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
     }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
     const bool is_static = a.inv_c != nullptr;
-    const bool is_gen = a.bits != 4;  // (never together with the static mode: the host refuses that)
+    const bool is_gen = a.bits != 4;
     const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + (is_static ? 0u : 4u * (64 * P / lpg)));
 
     // task numbers of a rank stay below 2^32 / segs (the kernel divides by multiplying)
@@ -535,10 +561,8 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         const dim3 grid(static_cast<unsigned>((a.n_tasks + 3) / 4), static_cast<unsigned>(a.n_ranks));
 #define TPQ_DIRECT_P(LPG, PP)                                                                       \
     case PP:                                                                                        \
-        e = is_gen ? launch_direct_lp<(LPG == 0 ? 4 : LPG), PP, false, true>(a, Y, codes, scale, zero, outl, \
-                                                                             lds, grid, s)            \
-                   : launch_direct_lp<LPG, PP, LPG == 0, false>(a, Y, codes, scale, zero, outl, lds,  \
-                                                                grid, s);                             \
+        e = is_gen ? launch_direct_lp<LPG, PP, LPG == 0, true>(a, Y, codes, scale, zero, outl, lds, grid, s) \
+                   : launch_direct_lp<LPG, PP, LPG == 0, false>(a, Y, codes, scale, zero, outl, lds, grid, s); \
         break;
 #define TPQ_DIRECT(LPG)                                                                      \
     switch (P) {                                                                             \

@@ -357,9 +357,9 @@ __global__ void k_plan_sblk_offsets(uint8_t *plan, int passes, PlanOffsets o)
 }
 
 // Static symmetric mode (Sec. 3): per device i and compacted position c (feature j =
-// src_of[c]): R = 2*max(-m, M), step = R/15, inv = 1/step; a vanishing range gives 0, 0.
+// src_of[c]): R = 2*max(-m, M), step = R/(2^bits - 1), inv = 1/step; a vanishing range gives 0, 0.
 __global__ void k_static_params(const uint8_t *plan, const float *__restrict__ m,
-                                const float *__restrict__ M, int E, int r, int stride,
+                                const float *__restrict__ M, int E, int r, int stride, float qmax,
                                 float *__restrict__ step, float *__restrict__ inv)
 {
     const PlanHeader *h = reinterpret_cast<const PlanHeader *>(plan);
@@ -373,7 +373,7 @@ __global__ void k_static_params(const uint8_t *plan, const float *__restrict__ m
         const float lo = -m[static_cast<int64_t>(i) * E + j], hi = M[static_cast<int64_t>(i) * E + j];
         float R = 2.0f * (lo > hi ? lo : hi);
         R += 0.0f;
-        const float q = R / 15.0f;
+        const float q = R / qmax;
         if (q >= 1e-30f) {
             d = q;
             v = 1.0f / q;
@@ -389,7 +389,8 @@ int launch_static_params(const tpq_layout *L, const void *plan, const float *m, 
     const int stride = 8 * chunks_padded_of(L->r);
     if (stride == 0) return TPQ_OK;
     const dim3 grid((stride + 255) / 256, n_ranks);
-    k_static_params<<<grid, 256, 0, s>>>(static_cast<const uint8_t *>(plan), m, M, L->E, L->r, stride, step, inv);
+    k_static_params<<<grid, 256, 0, s>>>(static_cast<const uint8_t *>(plan), m, M, L->E, L->r, stride,
+                                        static_cast<float>((1 << L->bits) - 1), step, inv);
     return hip_result(hipGetLastError());
 }
 

@@ -135,14 +135,3 @@ def test_llama_prefill_full_size(b):
     rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 13, replace=False)])
     L = _case(w.E, w.G, b, Ys, idx_for(w), rows=rows)
     assert tpq.payload_bits(L) == b + (16 - b) * w.k / w.E
-
-
-def test_static_mode_is_4_bits_only():
-    E, k, G = 512, 8, 128
-    L = tpq.layout_init(E, k, G, 6)
-    plan = gpu_plan(L, np.arange(0, 24, 3).astype(np.int32))
-    m = torch.full((2, E), -1.0, device="cuda")
-    M = torch.full((2, E), 1.0, device="cuda")
-    with pytest.raises(tpq.TpqError) as e:
-        tpq.static_params(L, plan, m, M)
-    assert e.value.code == tpq.ERR_UNSUPPORTED

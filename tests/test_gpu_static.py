@@ -43,17 +43,17 @@ def _ranges_from(Ys, shrink_every=5, dead_every=17):
 
 
 def _static_case(E, G, Ys, idx, m, M, rows=None, modes=((tpq.ACC_FP32, False), (tpq.ACC_FP32, True),
-                                                        (tpq.ACC_BF16, False)), ld_out=None):
+                                                        (tpq.ACC_BF16, False)), ld_out=None, bits=4):
     N, T = len(Ys), Ys[0].shape[0]
     k = int(idx.size)
     r = E - k
-    L = tpq.layout_init(E, k, G)
+    L = tpq.layout_init(E, k, G, bits)
     plan = gpu_plan(L, idx)
 
     # parameter tables: the oracle's (feature order) gathered into compacted order
     step, inv = tpq.static_params(L, plan, m, M)
     torch.cuda.synchronize()
-    step_ref, inv_ref = oracle.static_params(m.cpu().numpy(), M.cpu().numpy())
+    step_ref, inv_ref = oracle.static_params(m.cpu().numpy(), M.cpu().numpy(), bits=bits)
     comp = compaction(idx, E)
     W = tpq.static_table_floats(L)
     assert W % 512 == 0 and W >= r and (r == 0 or W - r < 512)
@@ -70,7 +70,7 @@ def _static_case(E, G, Ys, idx, m, M, rows=None, modes=((tpq.ACC_FP32, False), (
     refs = []
     for i, y in enumerate(Ys):
         Y = wl.to_bits(y if rows is None else y[torch.as_tensor(rows, device=y.device)])
-        ref = oracle.encode_static(Y, idx, inv_ref[i], threads=8)
+        ref = oracle.encode_static(Y, idx, inv_ref[i], threads=8, bits=bits)
         outl, codes, _, _ = msgs[i].to_dense(L)
         if rows is not None:
             outl, codes = outl[rows], codes[rows]
@@ -80,7 +80,7 @@ def _static_case(E, G, Ys, idx, m, M, rows=None, modes=((tpq.ACC_FP32, False), (
         assert bool((msgs[i].scale == CANARY).all().item()) and bool((msgs[i].zero == CANARY).all().item())
         if T > 0 and L.pitch_codes > 0:
             a = msgs[i].codes.cpu().numpy()[: L.pitch_codes * T].reshape(T, L.pitch_codes)
-            z = (L.code_bytes + 3) // 4 * 4
+            z = (L.code_bytes + 3) // 4 * 4 if bits == 4 else -(-r // 8) * bits   # written as zero up to here
             assert np.all(a[:, L.code_bytes:z] == 0) and np.all(a[:, z:] == CANARY)
         if T > 0 and L.pitch_outl > 0:
             a = msgs[i].outl.cpu().numpy()[: L.pitch_outl * T].reshape(T, L.pitch_outl)
@@ -100,11 +100,11 @@ def _static_case(E, G, Ys, idx, m, M, rows=None, modes=((tpq.ACC_FP32, False), (
         got = out.cpu().numpy().copy() if out_fp32 else wl.to_bits(out.contiguous())
         if rows is not None:
             got = got[rows]
-        want = oracle.decode_reduce_static(refs, idx, step_ref, accum, out_fp32=out_fp32, threads=8)
+        want = oracle.decode_reduce_static(refs, idx, step_ref, accum, out_fp32=out_fp32, threads=8, bits=bits)
         # tolerance of the bar: |gpu - oracle| <= rel * sum_i |x_hat_i| (+ half a bf16 ulp)
         mag = np.zeros(want.shape, np.float64)
         for i, ref in enumerate(refs):
-            one = oracle.decode_reduce_static([ref], idx, step_ref[i:i + 1], tpq.ACC_FP32, out_fp32=True)
+            one = oracle.decode_reduce_static([ref], idx, step_ref[i:i + 1], tpq.ACC_FP32, out_fp32=True, bits=bits)
             mag += np.abs(one.astype(np.float64))
         g = got.astype(np.float64) if out_fp32 else bits_to_f32(got).astype(np.float64)
         w_ = want.astype(np.float64) if out_fp32 else bits_to_f32(want).astype(np.float64)
@@ -277,3 +277,33 @@ def test_llama_prefill_full_size_static():
     rng = np.random.default_rng(3)
     rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 24, replace=False)])
     _static_case(w.E, w.G, Ys, idx_for(w), m, M, rows=rows)
+
+
+@pytest.mark.parametrize("b", (2, 3, 5, 6, 8))
+@pytest.mark.parametrize("E,k,G,T,N", [
+    (512, 8, 128, 16, 4),
+    (1032, 1, 128, 5, 3),      # odd r: a ragged last chunk
+    (1024, 0, 64, 7, 2),       # k = 0
+    (64, 64, 32, 3, 2),        # k = E
+    (5120, 80, 128, 6, 8),     # Llama width
+    (2048, 600, 64, 5, 3),     # many selected features
+    (8, 3, 32, 4, 2),
+    (1024, 16, 128, 3, 7),     # ranks not a multiple of the decode batch
+])
+def test_other_code_widths_static(E, k, G, T, N, b):
+    """The static quantiser at b bits (Sec. 4 / Fig. 3): step R / (2^b - 1), signed codes."""
+    Ys = _random_inputs(E, T, N, E * 31 + k + b)
+    rng = np.random.default_rng(E + k)
+    idx = np.sort(rng.choice(E, k, replace=False)).astype(np.int32)
+    m, M = _ranges_from(Ys)
+    _static_case(E, G, Ys, idx, m, M, ld_out=E + 16, bits=b)
+
+
+@pytest.mark.parametrize("b", (3, 8))
+def test_llama_prefill_full_size_static_other_widths(b):
+    w = wl.LLAMA_PREFILL
+    Ys = wl.partial_sums(w, device="cuda")
+    m, M = _ranges_from(Ys, shrink_every=3, dead_every=1001)
+    rng = np.random.default_rng(b)
+    rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 13, replace=False)])
+    _static_case(w.E, w.G, Ys, idx_for(w), m, M, rows=rows, bits=b)
