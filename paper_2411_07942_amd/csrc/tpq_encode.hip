@@ -172,8 +172,11 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
         raw[p] = __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_a4 *>(yrow + 4u * (d[p] & 0x3FFFu)));
     u32x4 win_b = {0u, 0u, 0u, 0u}, win_b2 = {0u, 0u, 0u, 0u};
-    if (ln < n_q) win_b = *reinterpret_cast<const u32x4_a4 *>(yrow + (slot8.y & 0x1FFFFu));
-    if (64u + ln < n_q) win_b2 = *reinterpret_cast<const u32x4_a4 *>(yrow + (rec2.y & 0x1FFFFu));
+    // (only where the next lane of the slot's pass does not load that window anyway)
+    const bool load_b = ln < n_q && (slot8.y & kDirLoadB8) != 0;
+    const bool load_b2 = 64u + ln < n_q && (rec2.y & kDirLoadB8) != 0;
+    if (load_b) win_b = *reinterpret_cast<const u32x4_a4 *>(yrow + (slot8.y & 0x1FFFFu));
+    if (load_b2) win_b2 = *reinterpret_cast<const u32x4_a4 *>(yrow + (rec2.y & 0x1FFFFu));
 
     constexpr int GPS = STATIC ? 0 : 64 * P / (STATIC ? 1 : LPG);  // groups per segment
     extern __shared__ u32x4 smem_direct[];
@@ -193,8 +196,16 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
             my_slot[p] = before + __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ball >> 32),
                                                            __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ball), 0u));
             before += static_cast<uint32_t>(__builtin_popcountll(ball));
-            if (has_slot) *reinterpret_cast<u32x4 *>(slots + 32u * my_slot[p]) = raw[p];
+            // the next lane's window: its first word completes an odd chunk, and all of it is
+            // the second window of most slots
             const uint32_t nb = __builtin_amdgcn_update_dpp(0u, raw[p].x, 0x130, 0xF, 0xF, false);
+            const uint32_t nby = __builtin_amdgcn_update_dpp(0u, raw[p].y, 0x130, 0xF, 0xF, false);
+            const uint32_t nbz = __builtin_amdgcn_update_dpp(0u, raw[p].z, 0x130, 0xF, 0xF, false);
+            const uint32_t nbw = __builtin_amdgcn_update_dpp(0u, raw[p].w, 0x130, 0xF, 0xF, false);
+            if (has_slot) {
+                *reinterpret_cast<u32x4 *>(slots + 32u * my_slot[p]) = raw[p];
+                *reinterpret_cast<u32x4 *>(slots + 32u * my_slot[p] + 16u) = u32x4{nb, nby, nbz, nbw};
+            }
             const uint32_t sh = (d[p] >> 10) & 16u;
             v[p].x = __builtin_amdgcn_alignbit(raw[p].y, raw[p].x, sh);
             v[p].y = __builtin_amdgcn_alignbit(raw[p].z, raw[p].y, sh);
@@ -202,13 +213,16 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
             v[p].w = __builtin_amdgcn_alignbit(nb, raw[p].w, sh);
         }
     }
-    if (ln < n_q) *reinterpret_cast<u32x4 *>(slots + 32u * ln + 16u) = win_b;
-    if (64u + ln < n_q) *reinterpret_cast<u32x4 *>(slots + 32u * (64u + ln) + 16u) = win_b2;
+    if (load_b) *reinterpret_cast<u32x4 *>(slots + 32u * ln + 16u) = win_b;
+    if (load_b2) *reinterpret_cast<u32x4 *>(slots + 32u * (64u + ln) + 16u) = win_b2;
     for (uint32_t q0 = 128; q0 < n_q; q0 += 64) {  // more than 128 slots in a segment: rare
         const uint32_t q = q0 + ln;
-        if (q < n_q)
-            *reinterpret_cast<u32x4 *>(slots + 32u * q + 16u) =
-                *reinterpret_cast<const u32x4_a4 *>(yrow + (dslot8[q_lo + q].y & 0x1FFFFu));
+        if (q < n_q) {
+            const uint32_t y1 = dslot8[q_lo + q].y;
+            if (y1 & kDirLoadB8)
+                *reinterpret_cast<u32x4 *>(slots + 32u * q + 16u) =
+                    *reinterpret_cast<const u32x4_a4 *>(yrow + (y1 & 0x1FFFFu));
+        }
     }
     wave_lds_fence();
 

@@ -66,7 +66,10 @@ namespace tpq {
 //   dslot8   uint32[2 * dslots]         per slot: word 0 = eight 4-bit half-word positions
 //                                       (feature e at bits 4e..4e+3) in the slot's 32 bytes,
 //                                       word 1 = byte offset of its second window in the
-//                                       row | kDirWide8 for a "wide" slot (see dirr)
+//                                       row | kDirWide8 for a "wide" slot (see dirr) |
+//                                       kDirLoadB8 unless the next lane of the pass loads
+//                                       exactly that window (the usual case: the owner then
+//                                       takes it from that lane's registers)
 //
 // Tables of the decoder's stores.  The 512 sums of a pass (in compacted order) go to
 // runs of consecutive output columns; selected columns and the pass's ends cut the
@@ -92,6 +95,8 @@ constexpr uint32_t kDirFar = 0x80000000u;   // in a dsel entry
 constexpr uint32_t kDir16Odd = 0x4000u;
 constexpr uint32_t kDir16Slot = 0x8000u;
 constexpr uint32_t kDirWide8 = 0x80000000u;  // in word 1 of a dslot8 entry
+constexpr uint32_t kDirLoadB8 = 0x40000000u; // in word 1 of a dslot8 entry: the second window is
+                                             // not what the next lane loads: fetch it
 
 struct PlanHeader {
     uint32_t magic;

@@ -214,8 +214,14 @@ __global__ void k_plan_dslots(uint8_t *plan, int E, int r, int chunks, int chunk
     *e16 = static_cast<uint16_t>((wa >> 1) | kDir16Slot);
     int wb = wa + 8;
     if (wb > E - 8) wb = E - 8;
+    // does the next lane of the pass load exactly the second window?
+    bool next_has_b = false;
+    if ((c & 63) != 63 && c + 1 < chunks) {
+        const int next_w = dflags[c + 1] ? dir_window_a(src, c + 1, E, r) : (src[8 * (c + 1)] & ~1);
+        next_has_b = next_w == wb;
+    }
     dslot8[2 * q] = nib;
-    dslot8[2 * q + 1] = static_cast<uint32_t>(2 * wb) | (wide ? kDirWide8 : 0u);
+    dslot8[2 * q + 1] = static_cast<uint32_t>(2 * wb) | (wide ? kDirWide8 : 0u) | (next_has_b ? 0u : kDirLoadB8);
 }
 
 // One thread per selected feature: the slot that holds its column.
