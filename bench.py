@@ -26,9 +26,9 @@ import torch
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak bandwidth
 # HBM bytes per tpq_encode launch on this workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 186.0 MB read
-# + 49.9 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
-ENCODE_TRAFFIC_BYTES = 235_820_000
+# scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 180.2 MB read
+# + 50.1 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
+ENCODE_TRAFFIC_BYTES = 230_280_000
 DECODE_TRAFFIC_BYTES = 84_570_000
 
 
