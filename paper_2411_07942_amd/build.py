@@ -68,6 +68,24 @@ def build_probe() -> str:
     return PROBE_BIN
 
 
+STREAM_SRC = os.path.join(ROOT, "tests", "probes", "stream_probe.hip")
+STREAM_BIN = os.path.join(ROOT, "tests", "probes", "stream_probe")
+
+
+def build_stream_probe() -> str:
+    """The stand-alone streaming microbenchmark quoted in the design notes (a measurement aid)."""
+    tmp = STREAM_BIN + ".tmp%d" % os.getpid()
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", STREAM_SRC, "-o", tmp]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for stream_probe.hip:\n" + r.stderr)
+    os.replace(tmp, STREAM_BIN)
+    return STREAM_BIN
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:]))
     print(build_probe())
+    print(build_stream_probe())
