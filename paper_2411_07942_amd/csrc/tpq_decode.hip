@@ -238,7 +238,10 @@ template <int LPG, int ACC, int OUT, bool GEN, bool FUSED>
 __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs codesp, RankPtrs scalep,
                                                      RankPtrs zerop, RankPtrs outlp)
 {
-    if (plan_header_bad(a.plan, a.E, a.k, a.G)) return;
+    // Nothing is stored unless the header says that the plan is good; the pass waves'
+    // loads do not wait for that answer (the message sections do not depend on the plan,
+    // and reads of the plan's tables are kept inside the plan buffer whatever it holds).
+    const bool bad = plan_header_bad(a.plan, a.E, a.k, a.G);
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t t = blockIdx.x;
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     if (task >= passes) {
         // ---- selected features ------------------------------------------------------
         const uint32_t p = (task - passes) * 64u + lane;
-        if (p >= static_cast<uint32_t>(a.k)) return;
+        if (bad || p >= static_cast<uint32_t>(a.k)) return;
         const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + a.off_idx);
         const uint32_t off_outl = t * static_cast<uint32_t>(a.pitch_outl);
         const uint32_t j = static_cast<uint32_t>(idx[p]);
@@ -296,8 +299,9 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     const uint32_t g = min(chunk / LPG, ng - 1u);
     // the pass's store entries: where they start, blocks, blocks + narrow entries
     const uint4 sp = reinterpret_cast<const uint4 *>(a.plan + a.off_spass)[task];
-    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + sp.x;
-    const uint32_t nb = sp.y, nall = sp.y + sp.z;
+    const uint32_t first = min(sp.x, static_cast<uint32_t>(a.sblk_cap));
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + first;
+    const uint32_t nall = min(sp.y + sp.z, static_cast<uint32_t>(a.sblk_cap) - first), nb = min(sp.y, nall);
     const uint32_t e0 = lane < nall ? entries[lane] : 0u;
     const uint32_t e1 = 64u + lane < nall ? entries[64u + lane] : 0u;
     // One 32-bit byte offset per section serves every rank (the host keeps
@@ -364,6 +368,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     uint32_t i0 = 0;
     for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
     if (i0 < N) batch(i0, std::false_type{});
+    if (bad) return;
     if constexpr (FUSED) {
         __shared__ u32x4 stage_f[4 * 128];
         store_pass_fused<OUT, ACC>(stage_f + wave * 128u, acc, out_row, lane, entries, nb, nall, e0, e1,
@@ -387,7 +392,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
 template <int ACC, int OUT, int R, bool GEN>
 __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs codesp, RankPtrs outlp)
 {
-    if (plan_header_bad(a.plan, a.E, a.k, a.G)) return;
+    const bool bad = plan_header_bad(a.plan, a.E, a.k, a.G);  // checked before any store
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t task = blockIdx.y * 4u + wave;
@@ -410,7 +415,7 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     if (task >= passes) {
         // ---- selected features ------------------------------------------------------
         const uint32_t p = (task - passes) * 64u + lane;
-        if (p >= static_cast<uint32_t>(a.k)) return;
+        if (bad || p >= static_cast<uint32_t>(a.k)) return;
         const int32_t *idx = reinterpret_cast<const int32_t *>(a.plan + a.off_idx);
         const uint32_t j = static_cast<uint32_t>(idx[p]);
         float acc[R];
@@ -457,8 +462,9 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     const uint32_t chunk = task * 64u + lane;
     // the pass's store entries: where they start, blocks, blocks + narrow entries
     const uint4 sp = reinterpret_cast<const uint4 *>(a.plan + a.off_spass)[task];
-    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + sp.x;
-    const uint32_t nb = sp.y, nall = sp.y + sp.z;
+    const uint32_t first = min(sp.x, static_cast<uint32_t>(a.sblk_cap));
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(a.plan + a.off_sblk) + first;
+    const uint32_t nall = min(sp.y + sp.z, static_cast<uint32_t>(a.sblk_cap) - first), nb = min(sp.y, nall);
     const uint32_t e0 = lane < nall ? entries[lane] : 0u;
     const uint32_t e1 = 64u + lane < nall ? entries[64u + lane] : 0u;
     // One 32-bit byte offset per section and row serves every rank (the host keeps
@@ -529,6 +535,7 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     uint32_t i0 = 0;
     for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
     if (i0 < N) batch_static(i0, std::false_type{});
+    if (bad) return;
     __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
@@ -597,6 +604,7 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
             a.off_idx = o.idx;
             a.off_spass = o.spass;
             a.off_sblk = o.sblk;
+            a.sblk_cap = sblk_cap_of(a.k, a.r);
         }
         RankPtrs codes = codes_in, scale = scale_in, zero = zero_in, outl = outl_in;
         a.T = a_in.T - row0 < rows_per_launch ? a_in.T - row0 : rows_per_launch;

@@ -234,7 +234,7 @@ struct DecodeArgs {
     const float *step_c;
     int32_t static_stride;
     // byte offsets of the plan's tables (what the header holds, known to the host too)
-    int32_t off_idx, off_spass, off_sblk;
+    int32_t off_idx, off_spass, off_sblk, sblk_cap;
 };
 
 // What a kernel checks before it trusts a plan: one wide scalar load, no branches between
