@@ -226,7 +226,7 @@ __device__ __forceinline__ void store_pass_fused(u32x4 *st, const float (&acc)[8
 // contiguous, so lines are written whole).
 // Outlier wave: lane p adds the ranks' bf16 values of outlier p and stores the sum at
 // its column.
-// grid: x = row, y = groups of 4 waves.
+// grid: (row, group of 4 waves) pairs, rounded up to a multiple of 8.
 // ---------------------------------------------------------------------------
 //
 // GEN selects code widths other than 4 bits (Sec. 4, the experiment that varies the bits
@@ -244,14 +244,21 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     const bool bad = plan_header_bad(a.plan, a.E, a.k, a.G);
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t t = blockIdx.x;
-    const uint32_t task = blockIdx.y * 4u + wave;
+    const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
+    // Each XCD works through one contiguous range of (row, wave group) pairs, a row's
+    // groups one after the other: the lines two neighbouring waves share (a row's scales
+    // and zeros, the ends of their code ranges, the output lines at a pass boundary)
+    // then meet in one L2, close in time.
+    const uint32_t ny = (passes + ((static_cast<uint32_t>(a.k) + 63u) >> 6) + 3u) >> 2;
+    const uint32_t logical = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const uint32_t t = logical / ny;
+    if (t >= static_cast<uint32_t>(a.T)) return;  // (the grid is rounded up to 8 blocks)
+    const uint32_t task = (logical - t * ny) * 4u + wave;
 
     constexpr uint32_t OB = OUT == TPQ_OUT_FP32 ? 4u : 2u;  // bytes per output value
     const uint32_t N = static_cast<uint32_t>(a.n_ranks);
     const uint32_t ng = static_cast<uint32_t>(a.ng);
     const uint32_t chunks = static_cast<uint32_t>(a.chunks);
-    const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
     uint8_t *const out_row = static_cast<uint8_t *>(a.out) + static_cast<int64_t>(t) * a.ldOut * OB;
 
     if (task >= passes) {
@@ -387,7 +394,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
 // roles, loads, accumulation order and stores as k_decode_pass, but a wave takes R
 // consecutive rows: the rows share the step loads, which otherwise outnumber the code
 // loads two to one.  Rows past the end are read as the last row and not stored.
-// grid: x = block of R rows, y = groups of 4 waves.
+// grid: (block of R rows, group of 4 waves) pairs, rounded up to a multiple of 8.
 // ---------------------------------------------------------------------------
 template <int ACC, int OUT, int R, bool GEN>
 __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs codesp, RankPtrs outlp)
@@ -395,14 +402,19 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     const bool bad = plan_header_bad(a.plan, a.E, a.k, a.G);  // checked before any store
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t task = blockIdx.y * 4u + wave;
+    const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
+    // (row block, wave group) pairs over the XCDs as in k_decode_pass
+    const uint32_t ny = (passes + ((static_cast<uint32_t>(a.k) + 63u) >> 6) + 3u) >> 2;
+    const uint32_t logical = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const uint32_t rb = logical / ny;
+    if (rb * static_cast<uint32_t>(R) >= static_cast<uint32_t>(a.T)) return;  // (grid rounded up to 8)
+    const uint32_t task = (logical - rb * ny) * 4u + wave;
 
     constexpr uint32_t OB = OUT == TPQ_OUT_FP32 ? 4u : 2u;  // bytes per output value
     const uint32_t N = static_cast<uint32_t>(a.n_ranks);
     const uint32_t chunks = static_cast<uint32_t>(a.chunks);
-    const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
     // the wave's rows; rows past the end are read as the last row and not stored
-    const uint32_t t0 = blockIdx.x * static_cast<uint32_t>(R);
+    const uint32_t t0 = rb * static_cast<uint32_t>(R);
     const uint32_t n_rows = min(static_cast<uint32_t>(R), static_cast<uint32_t>(a.T) - t0);
     uint32_t tr[R];
     uint8_t *out_row[R];
@@ -595,6 +607,8 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
     int64_t rows_per_launch = max_pitch > 0 ? (0x7FFFFFFFLL / max_pitch) : a_in.T;
     if (rows_per_launch > 0x7FFFFFFFLL) rows_per_launch = 0x7FFFFFFFLL;
     if (rows_per_launch < 1) return TPQ_ERR_SHAPE;
+    const int64_t ny = (tasks + 3) / 4;  // groups of 4 waves per row
+    if (rows_per_launch > 0x7FFFFFF0LL / ny) rows_per_launch = 0x7FFFFFF0LL / ny;  // (one-dimensional grid)
     const size_t ob = out_dtype == TPQ_OUT_FP32 ? 4 : 2;
     hipError_t e = hipSuccess;
     for (int64_t row0 = 0; row0 < a_in.T && e == hipSuccess; row0 += rows_per_launch) {
@@ -617,7 +631,8 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
             if (outl.p[i]) outl.p[i] = static_cast<const uint8_t *>(outl.p[i]) + row0 * a_in.pitch_outl;
         }
         const int rpw = rows_per_wave(a.step_c != nullptr, a.T, tasks);
-        const dim3 grid(static_cast<unsigned>((a.T + rpw - 1) / rpw), static_cast<unsigned>((tasks + 3) / 4));
+        // one dimension: (row block, wave group) pairs, dealt out over the XCDs by the kernel
+        const dim3 grid(static_cast<unsigned>(((a.T + rpw - 1) / rpw * ny + 7) / 8 * 8));
 #define TPQ_LAUNCH3(LPG, ACC, OUT) launch_rows<LPG, ACC, OUT>(rpw, grid, s, a, codes, scale, zero, outl)
 #define TPQ_LAUNCH2(LPG)                                                                     \
     do {                                                                                     \

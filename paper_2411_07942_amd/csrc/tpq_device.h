@@ -27,6 +27,16 @@ __device__ __forceinline__ float round_to_bf16(float f)
 }
 
 // 128-bit vector that the compiler may load / store as one instruction
+// Workgroups are handed to the chip's 8 XCDs in turn by linear id, and every XCD has an
+// L2 of its own.  For a grid whose x extent n is a multiple of 8 this turns the hardware
+// id into a logical index such that each XCD works through one contiguous range of
+// logical indices in order: neighbours in the index space then share an L2, close in
+// time (lines that two of them touch are fetched once and written whole).
+__device__ __forceinline__ uint32_t xcd_contiguous_index(uint32_t id, uint32_t n)
+{
+    return (id & 7u) * (n >> 3) + (id >> 3);
+}
+
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 // ... also at 2-byte alignment (gfx9 global memory accepts unaligned accesses in
