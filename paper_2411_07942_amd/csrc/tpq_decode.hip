@@ -360,13 +360,18 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
 #pragma unroll
                     for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(c[e], sc, ze);  // product exact
                 } else {
-                    uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
-                    asm volatile("" : "+v"(lo), "+v"(hi));
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        x[2 * e] = __builtin_fmaf(static_cast<float>((lo >> (8 * e)) & 0xFFu), sc, ze);
-                        x[2 * e + 1] = __builtin_fmaf(static_cast<float>((hi >> (8 * e)) & 0xFFu), sc, ze);
-                    }
+                    // one code per byte; the bytes 0 .. 15 read as FP8 (E4M3) are the codes
+                    // times 2^-9 (subnormals and the first binade have the same spacing), so
+                    // the scaled pair conversion turns two codes into floats at once
+                    const uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
+                    const f32x2 c02 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, false);
+                    const f32x2 c46 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, true);
+                    const f32x2 c13 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, false);
+                    const f32x2 c57 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, true);
+                    x[0] = __builtin_fmaf(c02.x, sc, ze); x[1] = __builtin_fmaf(c13.x, sc, ze);
+                    x[2] = __builtin_fmaf(c02.y, sc, ze); x[3] = __builtin_fmaf(c13.y, sc, ze);
+                    x[4] = __builtin_fmaf(c46.x, sc, ze); x[5] = __builtin_fmaf(c57.x, sc, ze);
+                    x[6] = __builtin_fmaf(c46.y, sc, ze); x[7] = __builtin_fmaf(c57.y, sc, ze);
                 }
                 accumulate8<ACC>(acc, x, i0 + j == 0);
             }

@@ -13,6 +13,8 @@
 //   8. one value rounded to bf16 by the pair conversion with a zero in the low half.
 //   9. v_cvt_pk_u8_f32 saturates at 255 (the clamp of the 8-bit code width).
 //  10. 2-, 4- and 8-byte global accesses at any byte address (code widths other than 4 bits).
+//  11. the scaled FP8 (E4M3) pair conversion with scale 2^9 turns the bytes 0 .. 15 into the
+//      floats 0 .. 15, from either half of the source word (4-bit codes to floats, two at once).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
@@ -104,6 +106,15 @@ __global__ void k_round1(const float *f, unsigned *out, int n)
 __global__ void k_perm(unsigned *out)
 {
     out[0] = __builtin_amdgcn_perm(0x88776655u, 0x44332211u, 0x07050301u);
+}
+
+__global__ void k_fp8_codes(float *out)
+{
+    const unsigned b = threadIdx.x & 15u;  // bytes b, b + 1, b + 2, b + 3 (mod 16)
+    const unsigned w = b | (((b + 1u) & 15u) << 8) | (((b + 2u) & 15u) << 16) | (((b + 3u) & 15u) << 24);
+    const f32x2 lo = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w, 512.0f, false);
+    const f32x2 hi = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w, 512.0f, true);
+    out[4 * b] = lo.x; out[4 * b + 1] = lo.y; out[4 * b + 2] = hi.x; out[4 * b + 3] = hi.y;
 }
 
 static unsigned bf16_rne(float f)
@@ -265,6 +276,17 @@ int main()
         }
         bad += memcmp(hb, after, 4096) != 0;
         printf("byte-aligned accesses : %s\n", bad ? "FAIL" : "ok");
+        fails += bad != 0;
+    }
+    {   // 11: 4-bit codes to floats through the FP8 pair conversion
+        float *d, h[64];
+        CK(hipMalloc(&d, sizeof h));
+        k_fp8_codes<<<1, 16>>>(d);
+        CK(hipMemcpy(h, d, sizeof h, hipMemcpyDeviceToHost));
+        int bad = 0;
+        for (int b = 0; b < 16; ++b)
+            for (int j = 0; j < 4; ++j) bad += h[4 * b + j] != (float)((b + j) & 15);
+        printf("fp8 pair conversion   : %s\n", bad ? "FAIL" : "ok");
         fails += bad != 0;
     }
     printf("%s\n", fails ? "HW PROBE FAILED" : "HW PROBE OK");
