@@ -242,6 +242,20 @@ def decode_reduce_fused(msgs, idx_sorted, E: int, G: int, addend=None, bias=None
     return out
 
 
+def hop(msg_in: Message, Y, idx_sorted, G: int, accum: int = ACC_BF16, threads: int = 1) -> Message:
+    """One step of a ring reduction (Sec. 5, the remark that the method could be adapted to ring
+    all-reduce; the paper fixes none of it): a device receives a message, adds its own partial sum
+    and sends the result on, quantised again.  Written out with the steps that exist already:
+    the received message is dequantised and the device's bf16 partial sum Y added as one more
+    term of the accumulation (decode_reduce_fused with the message as the only one and Y as the
+    addend), the bf16 result is the tensor that encode compresses."""
+    Y = _u16(Y)
+    T, E = Y.shape
+    V = decode_reduce_fused([msg_in], idx_sorted, E, G, addend=Y, bias=None, accum=accum,
+                            out_fp32=False, threads=threads)
+    return encode(V, idx_sorted, G, threads)
+
+
 def dequantize(msg: Message, idx_sorted, E: int, G: int, bits: int = 4) -> np.ndarray:
     """x_hat fp32 [T,E] of one message (the N = 1, fp32 case of decode_reduce)."""
     return decode_reduce([msg], idx_sorted, E, G, ACC_FP32, out_fp32=True, bits=bits)
