@@ -239,6 +239,43 @@ def section_fused(tpq, wl, args):
                     "tpq_decode_reduce_fused with both, bf16 chain and fp32 accumulate"}
 
 
+def section_hop(tpq, wl, args):
+    """Ring step at the Llama shape: 8 devices side by side in one launch, and one device alone
+    (its real share), against the same result from the two existing entry points (decode the one
+    message with the partial sum as addend into a bf16 tensor, then encode that tensor)."""
+    w = wl.LLAMA_PREFILL
+    N, T, E = w.N, w.T, w.E
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
+    tpq.plan_check(L, plan)
+    sets = []
+    for s in range(6):
+        Ys = wl.partial_sums(w, block=s, device=dev)
+        got = [tpq.Message(L, T, dev) for _ in range(N)]
+        tpq.encode(L, plan, Ys[1:] + Ys[:1], got)       # what each device has received
+        out = [tpq.Message(L, T, dev) for _ in range(N)]
+        tmp = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+        dec1 = tpq.decode_reduce_fused_call(L, plan, got[:1], tmp, Ys[0], None, tpq.ACC_BF16)
+        enc1 = tpq.encode_call(L, plan, [tmp], out[:1])
+
+        def two_calls(dec1=dec1, enc1=enc1):
+            dec1()
+            enc1()
+        sets.append(dict(hop=tpq.hop_call(L, plan, Ys, got, out, tpq.ACC_BF16),
+                         hop_fp32=tpq.hop_call(L, plan, Ys, got, out, tpq.ACC_FP32),
+                         hop1=tpq.hop_call(L, plan, Ys[:1], got[:1], out[:1], tpq.ACC_BF16),
+                         two_calls1=two_calls, keep=(Ys, got, out, tmp)))
+    t = {k: round(timed([s[k] for s in sets], 40) / len(sets), 2) for k in ("hop", "hop_fp32", "hop1", "two_calls1")}
+    W = L.wire_bytes_per_row
+    B = N * T * (2 * E + 2 * W)     # per launch: partial sums and received messages read, messages written
+    return {"section": "llama2_13b_prefill_ring_step", "us": t,
+            "hop_all_ranks_GBps": round(B / t["hop"] / 1e3, 1), "hop_one_rank_GBps": round(B / N / t["hop1"] / 1e3, 1),
+            "algorithmic_bytes": B,
+            "note": "tpq_hop for 8 devices in one launch (bf16 chain / fp32), for one device, and one device's step "
+                    "through tpq_decode_reduce_fused + tpq_encode with the bf16 sum in memory between them"}
+
+
 def section_static(tpq, wl, args):
     w = wl.LLAMA_PREFILL
     N, T, E = w.N, w.T, w.E
@@ -276,14 +313,14 @@ def section_static(tpq, wl, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused")
+    ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused,hop")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")
     import paper_2411_07942_amd as tpq
     import workloads as wl
     table = {"llama": section_llama, "gemma": section_gemma, "large": section_large,
-             "static": section_static, "bits": section_bits, "fused": section_fused}
+             "static": section_static, "bits": section_bits, "fused": section_fused, "hop": section_hop}
     for name in args.sections.split(","):
         print(json.dumps(table[name](tpq, wl, args)), flush=True)
 

@@ -168,6 +168,30 @@ int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y,
                uint16_t *const *scale, uint16_t *const *zero, uint16_t *const *outl,
                void *stream);
 
+/* ---- ring step (Sec. 5: the closing remark that the method, made for all-reduce as
+ * all-gather plus local reduction, could be adapted to ring all-reduce; the paper fixes
+ * no detail, the reading here is the plainest one) ------------------------------
+ * Device i has received a message and owns the partial sum Y[i]; what it sends on is
+ *     tpq_encode( bf16( D(message) (+) Y[i] ) )
+ * where D is the dequantisation of tpq_decode_reduce (selected features: the bf16 value
+ * itself) and (+) the accumulation's addition with Y[i] as its second term: fp32 sum
+ * rounded to bf16 once (TPQ_ACC_FP32), or D's value rounded to bf16 first
+ * (TPQ_ACC_BF16, the literal bf16 chain).  The result equals tpq_decode_reduce_fused
+ * over that one message with addend Y[i] and bf16 output, followed by tpq_encode, but
+ * the sum never goes to memory.  One launch serves n_ranks devices side by side, each with
+ * its own received message, partial sum and outgoing message, as tpq_encode does.
+ *   in_codes, in_scale, in_zero, in_outl  [host] arrays of n_ranks [device] pointers:
+ *         the received messages (layout L); must not overlap the outgoing ones
+ *   n_ranks  1 .. TPQ_MAX_HOP_RANKS
+ * Everything else as tpq_encode.  4-bit layouts only (TPQ_ERR_UNSUPPORTED otherwise). */
+#define TPQ_MAX_HOP_RANKS 16
+int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int64_t ldY,
+            int n_ranks, int64_t T, const uint8_t *const *in_codes,
+            const uint16_t *const *in_scale, const uint16_t *const *in_zero,
+            const uint16_t *const *in_outl, int accum, uint8_t *const *codes,
+            uint16_t *const *scale, uint16_t *const *zero, uint16_t *const *outl,
+            void *stream);
+
 /* ---- decode + reduce (Sec. 2 D^(i) and the sum; Fig. 2 caption) ------------
  * out[t][j] = sum over the n_ranks messages of x_hat (selected features: the
  * bf16 value itself), in ascending device order, in original feature order.

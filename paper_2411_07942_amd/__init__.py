@@ -32,7 +32,7 @@ EXPORTS = [
     "tpq_plan_bytes", "tpq_plan_build", "tpq_plan_check",
     "tpq_calibrate_workspace_bytes", "tpq_calibrate",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
-    "tpq_encode", "tpq_decode_reduce", "tpq_decode_reduce_fused",
+    "tpq_encode", "tpq_hop", "tpq_decode_reduce", "tpq_decode_reduce_fused",
     "tpq_static_table_floats", "tpq_static_params", "tpq_encode_static", "tpq_decode_reduce_static",
 ]
 
@@ -88,6 +88,7 @@ def _load():
     lib.tpq_calibrate_finalize_workspace_bytes.restype = sz
     lib.tpq_calibrate_finalize.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.tpq_encode.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, vp]
+    lib.tpq_hop.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, c_int, vp, vp, vp, vp, vp]
     lib.tpq_decode_reduce.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, c_int, c_int, vp, i64, vp]
     lib.tpq_decode_reduce_fused.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, vp, i64, vp, c_int, c_int,
                                             vp, i64, vp]
@@ -251,6 +252,35 @@ def encode(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], msgs: Seque
            stream=None) -> None:
     """Encode the ranks' partial sums Y[i] (bf16 [T,E]) into msgs[i] in one launch."""
     encode_call(L, plan, Y, msgs)(stream)
+
+
+def hop_call(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], in_msgs: Sequence[Message],
+             out_msgs: Sequence[Message], accum: int = ACC_BF16):
+    """Marshal a tpq_hop call once; the returned function(stream=None) issues it."""
+    lib = _load()
+    n = len(Y)
+    T = Y[0].shape[0]
+    ldY = Y[0].stride(0) if T > 1 else max(L.E, Y[0].stride(0))
+    for y in Y:
+        assert y.dtype == torch.bfloat16 and y.shape == Y[0].shape and y.stride(1) == 1
+        assert T <= 1 or y.stride(0) == ldY
+    assert len(in_msgs) == n and len(out_msgs) == n
+    args = (ctypes.byref(L), _ptr(plan), _ptr_array(Y, n), ldY, n, T,
+            _ptr_array([m.codes for m in in_msgs], n), _ptr_array([m.scale for m in in_msgs], n),
+            _ptr_array([m.zero for m in in_msgs], n), _ptr_array([m.outl for m in in_msgs], n), accum,
+            _ptr_array([m.codes for m in out_msgs], n), _ptr_array([m.scale for m in out_msgs], n),
+            _ptr_array([m.zero for m in out_msgs], n), _ptr_array([m.outl for m in out_msgs], n))
+    keep = (L, plan, list(Y), list(in_msgs), list(out_msgs))
+
+    def call(stream=None, _keep=keep):
+        _check(lib.tpq_hop(*args, _stream(stream)), "tpq_hop")
+    return call
+
+
+def hop(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], in_msgs: Sequence[Message],
+        out_msgs: Sequence[Message], accum: int = ACC_BF16, stream=None) -> None:
+    """Ring step: out_msgs[i] = encode(bf16(dequantised in_msgs[i] (+) Y[i])), one launch."""
+    hop_call(L, plan, Y, in_msgs, out_msgs, accum)(stream)
 
 
 def decode_reduce_call(L: Layout, plan: torch.Tensor, msgs: Sequence[Message], out: torch.Tensor,

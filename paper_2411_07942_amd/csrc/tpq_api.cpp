@@ -243,6 +243,56 @@ int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y, 
     return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream));
 }
 
+int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int64_t ldY,
+            int n_ranks, int64_t T, const uint8_t *const *in_codes, const uint16_t *const *in_scale,
+            const uint16_t *const *in_zero, const uint16_t *const *in_outl, int accum,
+            uint8_t *const *codes, uint16_t *const *scale, uint16_t *const *zero,
+            uint16_t *const *outl, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (n_ranks < 1 || n_ranks > TPQ_MAX_HOP_RANKS || T < 0 || ldY < L->E) return TPQ_ERR_SHAPE;
+    if (T * n_ranks > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
+    if ((ldY % 8) != 0) return TPQ_ERR_ALIGN;
+    if (!plan) return TPQ_ERR_NULL;
+    if (!aligned16(plan)) return TPQ_ERR_ALIGN;
+    RankPtrs pY, pc, ps, pz, po, ic, is, iz, io;
+    const bool quant = L->r > 0, keep = L->k > 0;
+    if ((rc = gather_ptrs(pY, reinterpret_cast<const void *const *>(Y), n_ranks, true))) return rc;
+    if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(ps, reinterpret_cast<const void *const *>(scale), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(pz, reinterpret_cast<const void *const *>(zero), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
+    if ((rc = gather_ptrs(ic, reinterpret_cast<const void *const *>(in_codes), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(is, reinterpret_cast<const void *const *>(in_scale), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(iz, reinterpret_cast<const void *const *>(in_zero), n_ranks, quant))) return rc;
+    if ((rc = gather_ptrs(io, reinterpret_cast<const void *const *>(in_outl), n_ranks, keep))) return rc;
+    if (T == 0) return TPQ_OK;
+    HopIn hin;
+    memset(&hin, 0, sizeof hin);
+    hin.accum = accum;
+    for (int i = 0; i < n_ranks; ++i) {
+        hin.codes[i] = ic.p[i];
+        hin.scale[i] = is.p[i];
+        hin.zero[i] = iz.p[i];
+        hin.outl[i] = io.p[i];
+    }
+    EncodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldY = ldY;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.bits = L->bits;
+    a.qmax = 15.0f;
+    return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream), &hin);
+}
+
 int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_t T,
                       const uint8_t *const *codes, const uint16_t *const *scale,
                       const uint16_t *const *zero, const uint16_t *const *outl, int accum,

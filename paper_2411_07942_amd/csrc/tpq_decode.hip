@@ -8,15 +8,6 @@
 
 namespace tpq {
 
-// A float rounded to bf16 (nearest even) and returned as a float again: the hardware's
-// pair conversion with a zero in the low half leaves exactly that in the register --
-// one instruction per value, against one and a half for converting pairs and taking
-// them apart again.
-__device__ __forceinline__ float round_via_bf16(float x)
-{
-    return __uint_as_float(pack_bf16x2(0.0f, x));
-}
-
 // The 8 B-bit fields of a 64-bit word as floats: field e at bits B*e .. B*e + B - 1.
 template <int B>
 __device__ __forceinline__ void unpack_codes(uint64_t w, float (&c)[8])

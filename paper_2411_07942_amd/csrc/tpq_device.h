@@ -59,6 +59,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// A float rounded to bf16 (nearest even) and returned as a float again: the hardware's
+// pair conversion with a zero in the low half leaves exactly that in the register --
+// one instruction per value, against one and a half for converting pairs and taking
+// them apart again.
+__device__ __forceinline__ float round_via_bf16(float x)
+{
+    return __uint_as_float(pack_bf16x2(0.0f, x));
+}
+
 // Orders one wavefront's LDS traffic: writes by any lane before this point are
 // seen by reads of any lane after it.  LDS operations of a wave execute in issue
 // order, so only the compiler has to be held back.

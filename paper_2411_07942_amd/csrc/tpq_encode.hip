@@ -10,7 +10,7 @@ namespace tpq {
 // k = E: nothing is quantised; the message is the row itself, column by column in
 // the order of the (complete) index set.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_copy_selected(EncodeArgs a, RankPtrs Yp, RankPtrs outlp)
+__global__ __launch_bounds__(256) void k_copy_selected(EncodeArgs a, RankPtrs Yp, RankPtrs outlp, HopIn hin)
 {
     const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
     if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
@@ -24,7 +24,13 @@ __global__ __launch_bounds__(256) void k_copy_selected(EncodeArgs a, RankPtrs Yp
     const uint16_t *y = static_cast<const uint16_t *>(Yp.p[rank]) + t * a.ldY;
     uint16_t *outl = reinterpret_cast<uint16_t *>(
         static_cast<uint8_t *>(const_cast<void *>(outlp.p[rank])) + t * a.pitch_outl);
-    outl[p] = y[idx[p]];
+    uint32_t val = y[idx[p]];
+    if (rank < static_cast<uint32_t>(kMaxHopRanks) && hin.outl[rank]) {  // ring step: received + own, in bf16
+        const uint16_t *in = reinterpret_cast<const uint16_t *>(
+            static_cast<const uint8_t *>(hin.outl[rank]) + t * a.pitch_outl);
+        val = pack_bf16x2(bf16_bits_to_f32(in[p]) + bf16_bits_to_f32(val), 0.0f) & 0xFFFFu;
+    }
+    outl[p] = static_cast<uint16_t>(val);
 }
 
 // x / 15, correctly rounded: the product with fl(1/15) is off by at most an ulp, the
@@ -97,6 +103,9 @@ __device__ __forceinline__ uint64_t pack_codes(uint32_t lo, uint32_t hi)
     return w;
 }
 
+#ifndef TPQ_HOP_OCC
+#define TPQ_HOP_OCC 5  // waves per SIMD of the ring step (15 more live registers than the encoder; 6: 2 % slower, 7: spills)
+#endif
 template <int P>
 struct DirectOcc {  // waves per SIMD the register budget is set for
     static constexpr int value = 8;
@@ -111,9 +120,15 @@ struct DirectOcc {  // waves per SIMD the register budget is set for
 // GEN selects code widths other than 4 bits (Sec. 4, the experiment that varies the
 // bits of the quantised features): 2^b - 1 steps over the group's range, and the 8
 // codes of a chunk are b bytes of the row's little-endian bit string.
-template <int LPG, int P, bool STATIC, bool GEN = false>
-__global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
-    EncodeArgs a, RankPtrs Yp, RankPtrs codesp, RankPtrs scalep, RankPtrs zerop, RankPtrs outlp)
+//
+// HOP makes the kernel a ring step (Sec. 5, the remark on ring all-reduce): what is
+// compressed is not the row of Y itself but the message the device has received,
+// dequantised, plus that row -- one more term of decode_reduce's accumulation, rounded
+// to bf16.  The received chunk's codes and its group's scale and zero are loaded with
+// the windows; the sums replace the features in registers before the group statistics.
+template <int LPG, int P, bool STATIC, bool GEN = false, bool HOP = false>
+__global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void k_encode_direct(
+    EncodeArgs a, RankPtrs Yp, RankPtrs codesp, RankPtrs scalep, RankPtrs zerop, RankPtrs outlp, HopIn hin)
 {
     const uint32_t ln = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -171,6 +186,20 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     for (int p = 0; p < P; ++p)
         raw[p] = __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_a4 *>(yrow + 4u * (d[p] & 0x3FFFu)));
+    uint32_t hop_w[P], hop_s[P], hop_z[P];  // HOP: the received chunk's codes, its group's scale and zero
+    if constexpr (HOP) {
+        const uint8_t *ic = static_cast<const uint8_t *>(hin.codes[rank]) + static_cast<int64_t>(t) * a.pitch_codes;
+        const uint8_t *is = static_cast<const uint8_t *>(hin.scale[rank]) + static_cast<int64_t>(t) * a.pitch_meta;
+        const uint8_t *iz = static_cast<const uint8_t *>(hin.zero[rank]) + static_cast<int64_t>(t) * a.pitch_meta;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t chunk = min((pass0 + p) * 64u + ln, static_cast<uint32_t>(a.chunks) - 1u);
+            const uint32_t g = min(chunk / (LPG ? LPG : 1), static_cast<uint32_t>(a.ng) - 1u);
+            hop_w[p] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(ic + 4u * chunk));
+            hop_s[p] = *reinterpret_cast<const uint16_t *>(is + 2u * g);
+            hop_z[p] = *reinterpret_cast<const uint16_t *>(iz + 2u * g);
+        }
+    }
     u32x4 win_b = {0u, 0u, 0u, 0u}, win_b2 = {0u, 0u, 0u, 0u};
     // (only where the next lane of the slot's pass does not load that window anyway)
     const bool load_b = ln < n_q && (slot8.y & kDirLoadB8) != 0;
@@ -240,6 +269,11 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
             const bool far = (e & kDirFar) != 0;
             uint32_t val = TPQ_LDS_HW(slots + (far ? 0u : e - 32u * q_lo));
             if (far) val = TPQ_HW(yrow + 2u * static_cast<uint32_t>(idx[s_lo + pc]));
+            if constexpr (HOP) {  // received + own, in bf16
+                const uint32_t in = reinterpret_cast<const uint16_t *>(
+                    static_cast<const uint8_t *>(hin.outl[rank]) + static_cast<int64_t>(t) * a.pitch_outl)[s_lo + pc];
+                val = pack_bf16x2(bf16_bits_to_f32(in) + bf16_bits_to_f32(val), 0.0f) & 0xFFFFu;
+            }
             if (p < n_sel) outl[p] = static_cast<uint16_t>(val);
         }
     }
@@ -273,6 +307,44 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
 #pragma unroll
     for (int p = 0; p < P; ++p)
         if (d[p] & kDir16Slot) v[p] = *reinterpret_cast<const u32x4 *>(slots + 32u * my_slot[p]);
+
+    if constexpr (HOP) {
+        // features <- bf16(x_hat (+) feature): x_hat = code * scale + zero as in decode_reduce,
+        // rounded to bf16 first in the bf16 chain.  The positions of a ragged last chunk
+        // past the row's end repeat the chunk's first sum (the received codes there are
+        // padding), so that they stay inside their group's range.
+        const bool chain = hin.accum == TPQ_ACC_BF16;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const float sc = bf16_bits_to_f32(hop_s[p]), ze = bf16_bits_to_f32(hop_z[p]);
+            const uint32_t lo = hop_w[p] & 0x0F0F0F0Fu, hi = (hop_w[p] >> 4) & 0x0F0F0F0Fu;
+            const f32x2 c02 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, false);
+            const f32x2 c46 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, true);
+            const f32x2 c13 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, false);
+            const f32x2 c57 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, true);
+            float x[8] = {__builtin_fmaf(c02.x, sc, ze), __builtin_fmaf(c13.x, sc, ze), __builtin_fmaf(c02.y, sc, ze),
+                          __builtin_fmaf(c13.y, sc, ze), __builtin_fmaf(c46.x, sc, ze), __builtin_fmaf(c57.x, sc, ze),
+                          __builtin_fmaf(c46.y, sc, ze), __builtin_fmaf(c57.y, sc, ze)};
+            if (chain) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = round_via_bf16(x[e]);
+            }
+            const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[2 * e] += bf16_lo_to_f32(wv[e]);
+                x[2 * e + 1] += bf16_hi_to_f32(wv[e]);
+            }
+            if (last_seg) {
+                const int n_valid = a.r - 8 * static_cast<int>((pass0 + p) * 64u + ln);
+#pragma unroll
+                for (int e = 1; e < 8; ++e)
+                    if (e >= n_valid) x[e] = x[0];
+            }
+            v[p] = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
+                         pack_bf16x2(x[6], x[7])};
+        }
+    }
 
     uint32_t *codes = reinterpret_cast<uint32_t *>(
         static_cast<uint8_t *>(const_cast<void *>(codesp.p[rank])) +
@@ -514,24 +586,25 @@ __global__ __launch_bounds__(256, DirectOcc<P>::value) void k_encode_direct(
     }
 }
 
-template <int LPG, int P, bool STATIC, bool GEN>
+template <int LPG, int P, bool STATIC, bool GEN, bool HOP = false>
 static hipError_t launch_direct_lp(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                                    const RankPtrs &scale, const RankPtrs &zero,
-                                   const RankPtrs &outl, size_t lds, dim3 grid, hipStream_t s)
+                                   const RankPtrs &outl, size_t lds, dim3 grid, hipStream_t s,
+                                   const HopIn &hin)
 {
     hipError_t e = hipSuccess;
     if (lds > 65536)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC, GEN>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC, GEN, HOP>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
-    k_encode_direct<LPG, P, STATIC, GEN><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl);
+    k_encode_direct<LPG, P, STATIC, GEN, HOP><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl, hin);
     return hipGetLastError();
 }
 
 // Direct path: one wave per (rank, row, segment).
 static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, const RankPtrs &codes_in,
                                 const RankPtrs &scale_in, const RankPtrs &zero_in,
-                                const RankPtrs &outl_in, hipStream_t s)
+                                const RankPtrs &outl_in, hipStream_t s, const HopIn *hop)
 {
     EncodeArgs a = a_in;
     const int lpg = a.G / 8;
@@ -571,12 +644,28 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
             if (zero.p[i]) zero.p[i] = static_cast<const uint8_t *>(zero.p[i]) + row0 * a.pitch_meta;
             if (outl.p[i]) outl.p[i] = static_cast<const uint8_t *>(outl.p[i]) + row0 * a.pitch_outl;
         }
+        HopIn hin = {};
+        if (hop) {
+            hin.accum = hop->accum;
+            for (int i = 0; i < a.n_ranks; ++i) {
+                hin.codes[i] = static_cast<const uint8_t *>(hop->codes[i]) + row0 * a.pitch_codes;
+                hin.scale[i] = static_cast<const uint8_t *>(hop->scale[i]) + row0 * a.pitch_meta;
+                hin.zero[i] = static_cast<const uint8_t *>(hop->zero[i]) + row0 * a.pitch_meta;
+                if (hop->outl[i]) hin.outl[i] = static_cast<const uint8_t *>(hop->outl[i]) + row0 * a.pitch_outl;
+            }
+        }
         a.n_tasks = a.T * a.segs;  // per rank
         const dim3 grid(static_cast<unsigned>((a.n_tasks + 3) / 4), static_cast<unsigned>(a.n_ranks));
 #define TPQ_DIRECT_P(LPG, PP)                                                                       \
     case PP:                                                                                        \
-        e = is_gen ? launch_direct_lp<LPG, PP, LPG == 0, true>(a, Y, codes, scale, zero, outl, lds, grid, s) \
-                   : launch_direct_lp<LPG, PP, LPG == 0, false>(a, Y, codes, scale, zero, outl, lds, grid, s); \
+        if constexpr (LPG != 0) {                                                                   \
+            if (hop) {                                                                              \
+                e = launch_direct_lp<LPG, PP, false, false, true>(a, Y, codes, scale, zero, outl, lds, grid, s, hin); \
+                break;                                                                              \
+            }                                                                                       \
+        }                                                                                           \
+        e = is_gen ? launch_direct_lp<LPG, PP, LPG == 0, true>(a, Y, codes, scale, zero, outl, lds, grid, s, hin) \
+                   : launch_direct_lp<LPG, PP, LPG == 0, false>(a, Y, codes, scale, zero, outl, lds, grid, s, hin); \
         break;
 #define TPQ_DIRECT(LPG)                                                                      \
     switch (P) {                                                                             \
@@ -600,12 +689,12 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
 
 int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                   const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl,
-                  hipStream_t s)
+                  hipStream_t s, const HopIn *hop)
 {
     const int lpg = a.G / 8;
     if (lpg != 4 && lpg != 8 && lpg != 16 && lpg != 32) return TPQ_ERR_UNSUPPORTED;
     if (a.T <= 0) return TPQ_OK;
-    if (a.r > 0) return hip_result(launch_direct(a, Y, codes, scale, zero, outl, s));
+    if (a.r > 0) return hip_result(launch_direct(a, Y, codes, scale, zero, outl, s, hop));
 
     // every feature selected: rows are handed over in blocks that fit the grid
     for (int64_t row0 = 0; row0 < a.T; row0 += 65535) {
@@ -618,7 +707,11 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
         }
         const dim3 grid(static_cast<unsigned>((a.k + 255) / 256), static_cast<unsigned>(b.T),
                         static_cast<unsigned>(a.n_ranks));
-        k_copy_selected<<<grid, 256, 0, s>>>(b, Yb, ob);
+        HopIn hb = {};
+        if (hop)
+            for (int i = 0; i < a.n_ranks; ++i)
+                hb.outl[i] = static_cast<const uint8_t *>(hop->outl[i]) + row0 * a.pitch_outl;
+        k_copy_selected<<<grid, 256, 0, s>>>(b, Yb, ob, hb);
     }
     return hip_result(hipGetLastError());
 }

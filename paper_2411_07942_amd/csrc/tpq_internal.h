@@ -197,6 +197,16 @@ struct RankPtrs {
     const void *p[TPQ_MAX_RANKS];
 };
 
+// Ring step: the message each rank has received (null pointers: plain encode).
+constexpr int kMaxHopRanks = TPQ_MAX_HOP_RANKS;
+struct HopIn {
+    const void *codes[kMaxHopRanks];
+    const void *scale[kMaxHopRanks];
+    const void *zero[kMaxHopRanks];
+    const void *outl[kMaxHopRanks];
+    int32_t accum;  // TPQ_ACC_*
+};
+
 struct EncodeArgs {
     const uint8_t *plan;
     int32_t E, k, G, r, ng, chunks, chunks_padded;
@@ -255,9 +265,10 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // kernel launchers (defined next to their kernels)
 int launch_plan_build(const tpq_layout *L, const int32_t *idx, void *plan, hipStream_t s);
+// hop: null for a plain encode, else the received messages (ring step)
 int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
                   const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl,
-                  hipStream_t s);
+                  hipStream_t s, const HopIn *hop = nullptr);
 int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
                   const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
                   hipStream_t s);
