@@ -43,8 +43,7 @@ def parse():
                     help="arithmetic of the sum over ranks in tpq_decode_reduce (the other mode is "
                          "timed beside it and reported under decode_reduce.other_mode)")
     ap.add_argument("--event-stride", type=int, default=8,
-                    help="kernel durations are sampled with HIP events on every n-th timed step "
-                         "(an event record costs about as much idle time as it measures)")
+                    help="kernel durations are sampled with HIP events on every n-th timed step")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calibrate-chunks", type=int, default=8)
     ap.add_argument("--copy-probe", action="store_true",
@@ -123,7 +122,13 @@ def main():
         step(sets[i % len(sets)])
     stride = max(1, args.event_stride)
     sampled = list(range(0, args.steps, stride))
-    ev = {i: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for i in sampled}
+    # HIP events attached to the sampled launches' own dispatches (tpq_time_next_launch): each
+    # pair brackets one kernel on the stream it runs on, with no idle time of its own
+    def new_event():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()           # creates the HIP event, whose handle the library is given
+        return e
+    ev = {i: [new_event() for _ in range(4)] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -133,28 +138,26 @@ def main():
             bufs[3]()
             bufs[4]()
         else:
-            e[0].record()
+            tpq.time_next_launch(e[0], e[1])
             bufs[3]()
-            e[1].record()
+            tpq.time_next_launch(e[2], e[3])
             bufs[4]()
-            e[2].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev.values()]))
-    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev.values()]))
+    dec_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in ev.values()]))
 
     # the other accumulate mode of tpq_decode_reduce, for the record (not part of `value`)
     other = tpq.ACC_BF16 if accum == tpq.ACC_FP32 else tpq.ACC_FP32
     other_calls = [tpq.decode_reduce_call(L, plan, b[1], b[2], other) for b in sets]
     for c in other_calls:
         c()
-    oe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(24)]
+    oe = [[new_event() for _ in range(2)] for _ in range(24)]
     torch.cuda.synchronize()
     for i, e in enumerate(oe):
-        e[0].record()
+        tpq.time_next_launch(e[0], e[1])
         other_calls[i % len(other_calls)]()
-        e[1].record()
     torch.cuda.synchronize()
     other_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in oe]))
 

@@ -10,6 +10,8 @@ static thread_local int g_last_hip_error = 0;
 
 void set_last_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
 
+thread_local LaunchTimer g_launch_timer = {nullptr, nullptr};
+
 int hip_result(hipError_t e)
 {
     if (e == hipSuccess) return TPQ_OK;
@@ -104,6 +106,13 @@ const char *tpq_strerror(int code)
 }
 
 int tpq_last_hip_error(void) { return g_last_hip_error; }
+
+int tpq_time_next_launch(void *start_event, void *stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return TPQ_ERR_NULL;
+    g_launch_timer = LaunchTimer{static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+    return TPQ_OK;
+}
 
 // ---- plan ---------------------------------------------------------------------
 

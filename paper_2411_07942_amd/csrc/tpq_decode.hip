@@ -570,21 +570,21 @@ static void launch_rows(int rpw, dim3 grid, hipStream_t s, const DecodeArgs &a, 
     if constexpr (LPG == 0) {
         if (a.bits != 4) {
             if (rpw == 4)
-                k_decode_static<ACC, OUT, 4, true><<<grid, 256, 0, s>>>(a, codes, outl);
+                launch_kernel(k_decode_static<ACC, OUT, 4, true>, grid, dim3(256), 0, s, a, codes, outl);
             else
-                k_decode_static<ACC, OUT, 1, true><<<grid, 256, 0, s>>>(a, codes, outl);
+                launch_kernel(k_decode_static<ACC, OUT, 1, true>, grid, dim3(256), 0, s, a, codes, outl);
         } else if (rpw == 4) {
-            k_decode_static<ACC, OUT, 4, false><<<grid, 256, 0, s>>>(a, codes, outl);
+            launch_kernel(k_decode_static<ACC, OUT, 4, false>, grid, dim3(256), 0, s, a, codes, outl);
         } else {
-            k_decode_static<ACC, OUT, 1, false><<<grid, 256, 0, s>>>(a, codes, outl);
+            launch_kernel(k_decode_static<ACC, OUT, 1, false>, grid, dim3(256), 0, s, a, codes, outl);
         }
     } else {
         if (a.addend || a.bias)  // (4 bits only: the host refuses the epilogue at other widths)
-            k_decode_pass<LPG, ACC, OUT, false, true><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+            launch_kernel(k_decode_pass<LPG, ACC, OUT, false, true>, grid, dim3(256), 0, s, a, codes, scale, zero, outl);
         else if (a.bits != 4)
-            k_decode_pass<LPG, ACC, OUT, true, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+            launch_kernel(k_decode_pass<LPG, ACC, OUT, true, false>, grid, dim3(256), 0, s, a, codes, scale, zero, outl);
         else
-            k_decode_pass<LPG, ACC, OUT, false, false><<<grid, 256, 0, s>>>(a, codes, scale, zero, outl);
+            launch_kernel(k_decode_pass<LPG, ACC, OUT, false, false>, grid, dim3(256), 0, s, a, codes, scale, zero, outl);
     }
 }
 

@@ -597,7 +597,7 @@ static hipError_t launch_direct_lp(const EncodeArgs &a, const RankPtrs &Y, const
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_direct<LPG, P, STATIC, GEN, HOP>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
-    k_encode_direct<LPG, P, STATIC, GEN, HOP><<<grid, 256, lds, s>>>(a, Y, codes, scale, zero, outl, hin);
+    launch_kernel(k_encode_direct<LPG, P, STATIC, GEN, HOP>, grid, dim3(256), lds, s, a, Y, codes, scale, zero, outl, hin);
     return hipGetLastError();
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "tpq.h"
@@ -260,6 +261,27 @@ __device__ __forceinline__ bool plan_header_bad(const uint8_t *plan, int E, int 
 int check_layout(const tpq_layout *L);  // TPQ_OK or an error code
 void set_last_hip_error(hipError_t e);
 int hip_result(hipError_t e);  // TPQ_OK, or records e and returns TPQ_ERR_HIP
+
+// One-shot timing request of the calling thread (tpq_time_next_launch): the next encode /
+// ring step / decode kernel is launched with these two events attached to its dispatch.
+struct LaunchTimer {
+    hipEvent_t start, stop;
+};
+extern thread_local LaunchTimer g_launch_timer;
+
+// kernel<<<grid, block, lds, s>>>(args...), with the pending timing events if there are any
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                          const Args &...args)
+{
+    if (g_launch_timer.start) {
+        const LaunchTimer t = g_launch_timer;
+        g_launch_timer = LaunchTimer{nullptr, nullptr};
+        hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), s, t.start, t.stop, 0u, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), s, args...);
+    }
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
