@@ -136,11 +136,25 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     const uint32_t passes = static_cast<uint32_t>(a.chunks_padded) >> 6;
     const uint32_t segs = static_cast<uint32_t>(a.segs);
     const uint32_t rank = blockIdx.y;
-    const uint32_t task = blockIdx.x * 4u + wave;
-    if (task >= static_cast<uint32_t>(a.n_tasks)) return;
-    // t = task / segs by multiplication (exact below 2^32 / segs, which the host keeps)
-    const uint32_t t = segs == 1 ? task : __umulhi(task, a.segs_magic);
-    const uint32_t seg = task - t * segs;
+    uint32_t t, seg;
+    bool active = true;
+    if constexpr (STATIC) {
+        // the four waves of a workgroup take the same segment of four consecutive rows, and
+        // share that segment's slice of the device's table through LDS (workgroup =
+        // (group of 4 rows, segment); the last group's waves past the last row only help
+        // with the table)
+        const uint32_t rg = segs == 1 ? blockIdx.x : __umulhi(blockIdx.x, a.segs_magic);
+        seg = blockIdx.x - rg * segs;
+        t = rg * 4u + wave;
+        active = t < static_cast<uint32_t>(a.T);
+        if (!active) t = static_cast<uint32_t>(a.T) - 1u;
+    } else {
+        const uint32_t task = blockIdx.x * 4u + wave;
+        if (task >= static_cast<uint32_t>(a.n_tasks)) return;
+        // t = task / segs by multiplication (exact below 2^32 / segs, which the host keeps)
+        t = segs == 1 ? task : __umulhi(task, a.segs_magic);
+        seg = task - t * segs;
+    }
     const uint32_t pass0 = seg * P, pass1 = min(pass0 + P, passes);
     const bool last_seg = pass1 == passes;
 
@@ -179,6 +193,20 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
         for (int p = 0; p < P; ++p) d[p] = (p & 1) ? (w4[p >> 1] >> 16) : (w4[p >> 1] & 0xFFFFu);
     }
 
+    // static mode: this thread's share of the segment's reciprocal steps (from L2; loaded
+    // first, so that they can be parked in LDS while the windows are still on their way)
+    u32x4 tab_in[(P * 128 + 255) / 256];
+    if constexpr (STATIC) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(
+            a.inv_c + static_cast<int64_t>(rank) * a.static_stride + 512u * pass0);
+        const uint32_t n4 = (pass1 - pass0) * 128u;  // 8 steps = two 16-byte units per chunk
+#pragma unroll
+        for (int i = 0; i < (P * 128 + 255) / 256; ++i) {
+            const uint32_t j = threadIdx.x + 256u * i;
+            tab_in[i] = src[min(j, n4 - 1u)];
+        }
+    }
+
     // windows: every lane its chunk's; lane q the second window of slot q
     const uint8_t *yrow = static_cast<const uint8_t *>(Yp.p[rank]) + static_cast<int64_t>(t) * a.ldY * 2;
     u32x4 raw[P];
@@ -211,6 +239,20 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     extern __shared__ u32x4 smem_direct[];
     uint8_t *slots = reinterpret_cast<uint8_t *>(smem_direct) + wave * (32u * a.patch_slots + 4u * GPS);
     uint32_t *l_meta = reinterpret_cast<uint32_t *>(slots + 32u * a.patch_slots);
+    // static mode: the workgroup's table slice behind the four waves' slots, the first and
+    // the second half of every chunk's 8 steps in arrays of their own (16-byte stride per lane)
+    u32x4 *l_tab = reinterpret_cast<u32x4 *>(reinterpret_cast<uint8_t *>(smem_direct) + 4u * 32u * a.patch_slots);
+    if constexpr (STATIC) {
+#pragma unroll
+        for (int i = 0; i < (P * 128 + 255) / 256; ++i) {
+            const uint32_t j = threadIdx.x + 256u * i;
+            if (j < static_cast<uint32_t>(P) * 128u) l_tab[(j & 1u) * (64u * P) + (j >> 1)] = tab_in[i];
+        }
+        if (!active) {
+            __syncthreads();
+            return;
+        }
+    }
 
     // A: windows -> slots (lanes that have one) and -> features (the others).  A lane's
     // slot number within the segment: the flagged chunks before its own.
@@ -357,13 +399,13 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
         // and differ at near-ties).  Adding 1.5 * 2^23 + 8 to the clamped product leaves
         // rint(.) + 8 in the sum's low byte: the sum's unit in the last place is 1, the
         // addition rounds to nearest even, and the offset is even, so ties fall as rint's.
-        const float *invr = a.inv_c + static_cast<int64_t>(rank) * a.static_stride;
+        __syncthreads();  // the table slice is complete (the only barrier: one per workgroup)
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const uint32_t chunk = (pass0 + p) * 64u + ln;  // < chunks_padded: inside the table
-            const float4 ia = *reinterpret_cast<const float4 *>(invr + 8u * chunk);
-            const float4 ib = *reinterpret_cast<const float4 *>(invr + 8u * chunk + 4u);
-            const float iv[8] = {ia.x, ia.y, ia.z, ia.w, ib.x, ib.y, ib.z, ib.w};
+            const u32x4 ia = l_tab[p * 64 + ln], ib = l_tab[64 * P + p * 64 + ln];
+            const float iv[8] = {__uint_as_float(ia.x), __uint_as_float(ia.y), __uint_as_float(ia.z),
+                                 __uint_as_float(ia.w), __uint_as_float(ib.x), __uint_as_float(ib.y),
+                                 __uint_as_float(ib.z), __uint_as_float(ib.w)};
             const uint32_t wv[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
             if constexpr (GEN) {
                 // b-bit codes: clamp to -2^(b-1) .. 2^(b-1) - 1, then the same rounding by
@@ -628,7 +670,9 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
     const bool is_static = a.inv_c != nullptr;
     const bool is_gen = a.bits != 4;
-    const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + (is_static ? 0u : 4u * (64 * P / lpg)));
+    // per wave: slots (+ the groups' scale / zero pairs); static mode: + the workgroup's table slice
+    const size_t lds = 4 * (32u * static_cast<size_t>(a.patch_slots) + (is_static ? 0u : 4u * (64 * P / lpg))) +
+                       (is_static ? 64u * 32u * static_cast<size_t>(P) : 0u);
 
     // task numbers of a rank stay below 2^32 / segs (the kernel divides by multiplying)
     // and the grid's x extent below 2^31: hand over the rows in blocks
@@ -655,7 +699,9 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
             }
         }
         a.n_tasks = a.T * a.segs;  // per rank
-        const dim3 grid(static_cast<unsigned>((a.n_tasks + 3) / 4), static_cast<unsigned>(a.n_ranks));
+        // workgroups of 4 tasks; static mode: (group of 4 rows, segment) pairs
+        const dim3 grid(static_cast<unsigned>(is_static ? (a.T + 3) / 4 * a.segs : (a.n_tasks + 3) / 4),
+                        static_cast<unsigned>(a.n_ranks));
 #define TPQ_DIRECT_P(LPG, PP)                                                                       \
     case PP:                                                                                        \
         if constexpr (LPG != 0) {                                                                   \
