@@ -511,6 +511,12 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
         for (int j = 0; j < 4; ++j) {
             if (FULL || i0 + j < N) {  // uniform
                 const float st[8] = {sa[j].x, sa[j].y, sa[j].z, sa[j].w, sb[j].x, sb[j].y, sb[j].z, sb[j].w};
+                // (field - 8) * step as one fused multiply-add per value: -8 * step is exact, so
+                // field * step - 8 * step is rounded once, from the same exact product; shared
+                // by the wave's rows
+                float m8[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) m8[e] = -8.0f * st[e];
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
                     float x[8];
@@ -527,13 +533,16 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
 #pragma unroll
                         for (int e = 0; e < 8; ++e) x[e] = (c[e] - half) * st[e];
                     } else {
-                        uint32_t lo = w[rr][j] & 0x0F0F0F0Fu, hi = (w[rr][j] >> 4) & 0x0F0F0F0Fu;
-                        asm volatile("" : "+v"(lo), "+v"(hi));
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            x[2 * e] = (static_cast<float>((lo >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e];
-                            x[2 * e + 1] = (static_cast<float>((hi >> (8 * e)) & 0xFFu) - 8.0f) * st[2 * e + 1];
-                        }
+                        // fields to floats two at a time (FP8 pair conversion, as in k_decode_pass)
+                        const uint32_t lo = w[rr][j] & 0x0F0F0F0Fu, hi = (w[rr][j] >> 4) & 0x0F0F0F0Fu;
+                        const f32x2 c02 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, false);
+                        const f32x2 c46 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(lo, 512.0f, true);
+                        const f32x2 c13 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, false);
+                        const f32x2 c57 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(hi, 512.0f, true);
+                        x[0] = __builtin_fmaf(c02.x, st[0], m8[0]); x[1] = __builtin_fmaf(c13.x, st[1], m8[1]);
+                        x[2] = __builtin_fmaf(c02.y, st[2], m8[2]); x[3] = __builtin_fmaf(c13.y, st[3], m8[3]);
+                        x[4] = __builtin_fmaf(c46.x, st[4], m8[4]); x[5] = __builtin_fmaf(c57.x, st[5], m8[5]);
+                        x[6] = __builtin_fmaf(c46.y, st[6], m8[6]); x[7] = __builtin_fmaf(c57.y, st[7], m8[7]);
                     }
                     accumulate8<ACC>(acc[rr], x, i0 + j == 0);
                 }
