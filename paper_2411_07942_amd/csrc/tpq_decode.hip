@@ -312,8 +312,10 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
     // 8 ranks at a time: all 24 loads first, then the arithmetic.  FULL batches index
     // the pointer tables with constants (one wide scalar load each); the last, partial
     // batch guards every rank.
-    auto batch = [&](uint32_t i0, auto full_tag) {
+    // (the code width is a compile-time constant inside: one copy of the loop per width)
+    auto batch = [&](uint32_t i0, auto full_tag, auto bits_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int BITS = decltype(bits_tag)::value;
         uint32_t w[8], sb[8], zb[8];
         uint64_t wq[8];  // GEN
         const void *const *pc = codesp.p + i0;
@@ -341,13 +343,7 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
                 float x[8];
                 if constexpr (GEN) {
                     float c[8];
-                    switch (a.bits) {
-                    case 2: unpack_codes<2>(wq[j], c); break;
-                    case 3: unpack_codes<3>(wq[j], c); break;
-                    case 5: unpack_codes<5>(wq[j], c); break;
-                    case 6: unpack_codes<6>(wq[j], c); break;
-                    default: unpack_codes<8>(wq[j], c); break;
-                    }
+                    unpack_codes<BITS>(wq[j], c);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(c[e], sc, ze);  // product exact
                 } else {
@@ -368,9 +364,22 @@ __global__ __launch_bounds__(256) void k_decode_pass(DecodeArgs a, RankPtrs code
             }
         }
     };
-    uint32_t i0 = 0;
-    for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{});
-    if (i0 < N) batch(i0, std::false_type{});
+    auto run = [&](auto bits_tag) {
+        uint32_t i0 = 0;
+        for (; i0 + 8 <= N; i0 += 8) batch(i0, std::true_type{}, bits_tag);
+        if (i0 < N) batch(i0, std::false_type{}, bits_tag);
+    };
+    if constexpr (GEN) {
+        switch (a.bits) {
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+        }
+    } else {
+        run(std::integral_constant<int, 4>{});
+    }
     if (bad) return;
     if constexpr (FUSED) {
         __shared__ u32x4 stage_f[4 * 128];
@@ -485,8 +494,9 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
     float acc[R][8];
 
     // static mode, 4 ranks at a time: a code word per row and 8 steps each
-    auto batch_static = [&](uint32_t i0, auto full_tag) {
+    auto batch_static = [&](uint32_t i0, auto full_tag, auto bits_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int BITS = decltype(bits_tag)::value;  // (one copy of the loop per width)
         uint32_t w[R][4];
         uint64_t wq[R][4];  // GEN
         float4 sa[4], sb[4];
@@ -522,14 +532,8 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
                     float x[8];
                     if constexpr (GEN) {
                         float c[8];
-                        switch (a.bits) {
-                        case 2: unpack_codes<2>(wq[rr][j], c); break;
-                        case 3: unpack_codes<3>(wq[rr][j], c); break;
-                        case 5: unpack_codes<5>(wq[rr][j], c); break;
-                        case 6: unpack_codes<6>(wq[rr][j], c); break;
-                        default: unpack_codes<8>(wq[rr][j], c); break;
-                        }
-                        const float half = static_cast<float>(1u << (static_cast<uint32_t>(a.bits) - 1u));
+                        unpack_codes<BITS>(wq[rr][j], c);
+                        constexpr float half = static_cast<float>(1u << (BITS - 1));
 #pragma unroll
                         for (int e = 0; e < 8; ++e) x[e] = (c[e] - half) * st[e];
                     } else {
@@ -549,9 +553,22 @@ __global__ __launch_bounds__(256) void k_decode_static(DecodeArgs a, RankPtrs co
             }
         }
     };
-    uint32_t i0 = 0;
-    for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{});
-    if (i0 < N) batch_static(i0, std::false_type{});
+    auto run = [&](auto bits_tag) {
+        uint32_t i0 = 0;
+        for (; i0 + 4 <= N; i0 += 4) batch_static(i0, std::true_type{}, bits_tag);
+        if (i0 < N) batch_static(i0, std::false_type{}, bits_tag);
+    };
+    if constexpr (GEN) {
+        switch (a.bits) {
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+        }
+    } else {
+        run(std::integral_constant<int, 4>{});
+    }
     if (bad) return;
     __shared__ u32x4 stage[4 * 64 * (OUT == TPQ_OUT_FP32 ? 2 : 1)];
 #pragma unroll
