@@ -120,6 +120,17 @@ def test_llama_prefill_full_size():
     _case(w.E, w.G, Ys, Ys[1:] + Ys[:1], idx_for(w), rows=rows)
 
 
+def test_large_prefill_full_size():
+    """16 devices side by side, [16384 x 8192], 4.5 bits (k = 341), group 64: sampled rows."""
+    w = [v for v in wl.large_variants() if v.k == 341 and v.G == 64][0]
+    Ys = wl.partial_sums(w, device="cuda")
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 13, replace=False)])
+    _case(w.E, w.G, Ys, Ys[3:] + Ys[:3], idx_for(w), rows=rows)
+    del Ys
+    torch.cuda.empty_cache()
+
+
 def test_argument_errors():
     E, k, G = 512, 8, 128
     idx = np.arange(0, 24, 3).astype(np.int32)
