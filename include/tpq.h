@@ -120,7 +120,8 @@ int tpq_last_hip_error(void); /* hipError_t of the most recent TPQ_ERR_HIP on th
  * dispatch: afterwards hipEventElapsedTime(start, stop) is that kernel's duration on
  * the GPU, without the idle time that separately recorded events put around a launch.
  * One launch only (a call that splits its rows over several launches times the first);
- * both NULL cancels a pending request. */
+ * a request stays pending, also across calls that fail their argument checks, until a
+ * kernel is launched or both NULL cancel it. */
 int tpq_time_next_launch(void *start_event, void *stop_event);
 
 /* ---- plan: device tables derived from the static outlier index set -------
