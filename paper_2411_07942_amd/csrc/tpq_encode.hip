@@ -615,16 +615,36 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
         }
         return;
     }
+    // The segment's codes are one contiguous piece of the row (256 bytes per pass).  They leave
+    // as 128-bit stores: every lane parks its P words in LDS in chunk order and takes four
+    // consecutive ones back -- 1 KB per store instruction instead of 256 bytes, which the
+    // memory system takes markedly better (tests/probes/stream_probe: "16-byte stores").
+    // A last segment's final one to three words go out singly, so that nothing past the
+    // row's codes is written.
+    {
+        // (in the wave's slot area, which nothing reads any more; the host gives it 256 P bytes at least)
+        uint32_t *l_codes = reinterpret_cast<uint32_t *>(slots);
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const uint32_t chunk = (pass0 + p) * 64u + ln;
-        if (last_seg) {
-            const int n_valid = a.r - 8 * static_cast<int>(chunk);
-            if (n_valid < 8) w[p] &= (1u << (4 * (n_valid & 7))) - 1u;
-            if (chunk < static_cast<uint32_t>(a.chunks)) __builtin_nontemporal_store(w[p], codes + chunk);
-        } else {
-            __builtin_nontemporal_store(w[p], codes + chunk);
+        for (int p = 0; p < P; ++p) {
+            if (last_seg) {
+                const int n_valid = a.r - 8 * static_cast<int>((pass0 + p) * 64u + ln);
+                if (n_valid < 8) w[p] &= (1u << (4 * (n_valid & 7))) - 1u;
+            }
+            l_codes[p * 64 + ln] = w[p];
         }
+        wave_lds_fence();
+        const uint32_t nc = last_seg ? static_cast<uint32_t>(a.chunks) - pass0 * 64u : 64u * P;  // chunks to store
+        const uint32_t full = nc >> 2;
+        uint8_t *dst = reinterpret_cast<uint8_t *>(codes) + 256u * pass0;
+#pragma unroll
+        for (uint32_t u0 = 0; u0 < 16u * P; u0 += 64) {
+            const uint32_t u = u0 + ln;
+            if (u < full)
+                __builtin_nontemporal_store(reinterpret_cast<const u32x4 *>(l_codes)[u],
+                                            reinterpret_cast<u32x4 *>(dst + 16u * u));
+        }
+        const uint32_t c = 4u * full + ln;
+        if (c < nc) __builtin_nontemporal_store(l_codes[c], reinterpret_cast<uint32_t *>(dst + 4u * c));
     }
 }
 
@@ -668,6 +688,7 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         a.off_drec2 = o.drec2;
     }
     a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
+    if (a.patch_slots < 8 * P) a.patch_slots = 8 * P;  // (the codes pass through the same area: 256 P bytes)
     const bool is_static = a.inv_c != nullptr;
     const bool is_gen = a.bits != 4;
     // per wave: slots (+ the groups' scale / zero pairs); static mode: + the workgroup's table slice
