@@ -124,6 +124,36 @@ __global__ __launch_bounds__(256) void k_encode_like(const unsigned short *__res
     }
 }
 
+// The encoder's reads alone: two waves per row, five 4-byte-aligned 128-bit loads each.
+// TAB = 1: the loads' offsets come from a 32-byte record per lane and segment first (a
+// 4 KB table that every row reads again, as the encoder's plan records are).
+template <int TAB>
+__global__ __launch_bounds__(256) void k_encode_reads(const unsigned short *__restrict__ src,
+                                                      const u4 *__restrict__ table, u4 *__restrict__ sink,
+                                                      unsigned rows)
+{
+    const unsigned lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned task = blockIdx.x * 4 + wave;
+    const unsigned row = task >> 1, seg = task & 1;
+    if (row >= rows) return;
+    const unsigned short *s = src + (size_t)row * 5120;
+    unsigned off[5];
+    if (TAB) {
+        const u4 a = table[(seg * 64 + lane) * 2], b = table[(seg * 64 + lane) * 2 + 1];
+        off[0] = a.x; off[1] = a.y; off[2] = a.z; off[3] = a.w; off[4] = b.x;
+    } else {
+#pragma unroll
+        for (int p = 0; p < 5; ++p) off[p] = ((seg * 5 + p) * 64 + lane) * 8 + 2;
+    }
+    u4 acc = {0, 0, 0, 0};
+    u4 v[5];
+#pragma unroll
+    for (int p = 0; p < 5; ++p) v[p] = __builtin_nontemporal_load((const u4_a2 *)(s + (off[p] < 5110 ? off[p] : 5110)));
+#pragma unroll
+    for (int p = 0; p < 5; ++p) acc ^= v[p];
+    if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) sink[0] = acc;
+}
+
 template <typename F>
 static float time_ms(F f, int n = 10)
 {
@@ -178,6 +208,24 @@ int main()
         ms = time_ms([&](int i) { k_decode_like<<<R * 12 / 4, 256>>>(c, sc, ze, dst[i % NB], R); });
         printf("decode-like       : %7.1f GB/s (8 x 256 B + 16 x 2 B read, 1 KB written per wave)\n", dec_bytes / ms / 1e6);
         const double enc_bytes = (double)R * (10240 + 2520 + 160);
+        {
+            u4 *tab;
+            static u4 htab[256];
+            for (unsigned sg = 0; sg < 2; ++sg)
+                for (unsigned l = 0; l < 64; ++l) {
+                    unsigned o[5];
+                    for (unsigned p = 0; p < 5; ++p) o[p] = ((sg * 5 + p) * 64 + l) * 8 + 2;
+                    htab[(sg * 64 + l) * 2] = u4{o[0], o[1], o[2], o[3]};
+                    htab[(sg * 64 + l) * 2 + 1] = u4{o[4], 0, 0, 0};
+                }
+            CK(hipMalloc(&tab, sizeof htab));
+            CK(hipMemcpy(tab, htab, sizeof htab, hipMemcpyHostToDevice));
+            const size_t rows5 = bytes / 10240;
+            ms = time_ms([&](int i) { k_encode_reads<0><<<(unsigned)(rows5 * 2 / 4), 256>>>(src[i % NB], tab, sink, (unsigned)rows5); });
+            printf("encoder's reads   : %7.1f GB/s (two waves per row, five loads each)\n", (double)rows5 * 10240 / ms / 1e6);
+            ms = time_ms([&](int i) { k_encode_reads<1><<<(unsigned)(rows5 * 2 / 4), 256>>>(src[i % NB], tab, sink, (unsigned)rows5); });
+            printf("... offsets loaded: %7.1f GB/s (a 32-byte record per lane first)\n", (double)rows5 * 10240 / ms / 1e6);
+        }
 #define TPQ_ENC_LIKE(VAR)                                                                              \
     time_ms([&](int i) {                                                                               \
         k_encode_like<VAR><<<R * 2 / 4, 256>>>(src[i % NB], const_cast<unsigned char *>(c.p[i % 8]),   \
