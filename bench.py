@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak bandwidth
 # HBM bytes per tpq_encode launch on this workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # scaled by a 256 MiB device copy (profiles/llama2_13b_prefill_encode_decode.md): 180.2 MB read
 # + 50.1 MB written.  bench.py cannot collect counters itself; the figure is refreshed with the profile.
-ENCODE_TRAFFIC_BYTES = 230_580_000
+ENCODE_TRAFFIC_BYTES = 227_790_000
 DECODE_TRAFFIC_BYTES = 70_800_000
 
 
