@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_PKG, "libtpq.so")
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_INDEX, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP = (
     -1, -2, -3, -4, -5, -6, -7)
-ACC_FP32, ACC_BF16 = 0, 1
+ACC_FP32, ACC_BF16, ACC_FAST = 0, 1, 2
 OUT_BF16, OUT_FP32 = 0, 1
 MAX_RANKS = 64
 MAX_E = 32768

@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libtpq.so")
 
-SOURCES = ["tpq_api.cpp", "tpq_plan.hip", "tpq_calibrate.hip", "tpq_encode.hip", "tpq_decode.hip"]
+SOURCES = ["tpq_api.cpp", "tpq_plan.hip", "tpq_calibrate.hip", "tpq_encode.hip", "tpq_decode.hip", "tpq_decode_rows.hip", "tpq_encode_rows.hip"]
 
 # -ffp-contract=off: codes, scales and sums must match a non-fused IEEE evaluation.
 # -fno-honor-nans: inputs are finite by contract; without it every min / max drags a
@@ -41,7 +41,7 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(extra_flags=(), jobs: int = 5) -> str:
+def build(extra_flags=(), jobs: int = 7) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))

@@ -309,7 +309,7 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
 {
     int rc = check_layout(L);
     if (rc) return rc;
-    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16 && accum != TPQ_ACC_FAST) return TPQ_ERR_UNSUPPORTED;
     if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
     if (T > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
@@ -346,7 +346,7 @@ int tpq_decode_reduce_fused(const tpq_layout *L, const void *plan, int n_ranks, 
     int rc = check_layout(L);
     if (rc) return rc;
     if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;  // the epilogue is built for 4-bit codes
-    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16 && accum != TPQ_ACC_FAST) return TPQ_ERR_UNSUPPORTED;
     if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
     if (T > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;
@@ -442,7 +442,7 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
 {
     int rc = check_layout(L);
     if (rc) return rc;
-    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16) return TPQ_ERR_UNSUPPORTED;
+    if (accum != TPQ_ACC_FP32 && accum != TPQ_ACC_BF16 && accum != TPQ_ACC_FAST) return TPQ_ERR_UNSUPPORTED;
     if (out_dtype != TPQ_OUT_BF16 && out_dtype != TPQ_OUT_FP32) return TPQ_ERR_UNSUPPORTED;
     if (n_ranks < 1 || n_ranks > TPQ_MAX_RANKS || T < 0 || ldOut < L->E) return TPQ_ERR_SHAPE;
     if (T > 0x7FFFFFFFLL) return TPQ_ERR_SHAPE;

@@ -141,4 +141,24 @@ __device__ __forceinline__ void group_minmax_n(float (&mn)[N], float (&mx)[N])
     }
 }
 
+// x / 15, correctly rounded: the product with fl(1/15) is off by at most an ulp, the
+// remainder x - 15 q is exact in a fused multiply-add, and one more of them lands on the
+// rounded quotient (checked against the division for every positive float).
+__device__ __forceinline__ float div_by_15(float x)
+{
+    const float y = 0x1.111112p-4f;
+    const float q = x * y;
+    const float r = __builtin_fmaf(-15.0f, q, x);
+    return __builtin_fmaf(r, y, q);
+}
+
+// 1 / s for a bf16-valued scale s: hardware reciprocal (1 ulp) and one Newton step.
+// Equal to the IEEE quotient for every bf16 s with a normal reciprocal.
+__device__ __forceinline__ float reciprocal_of_scale(float s)
+{
+    const float y = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, y, 1.0f);
+    return __builtin_fmaf(e, y, y);
+}
+
 }  // namespace tpq

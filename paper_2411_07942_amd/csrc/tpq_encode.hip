@@ -33,26 +33,6 @@ __global__ __launch_bounds__(256) void k_copy_selected(EncodeArgs a, RankPtrs Yp
     outl[p] = static_cast<uint16_t>(val);
 }
 
-// x / 15, correctly rounded: the product with fl(1/15) is off by at most an ulp, the
-// remainder x - 15 q is exact in a fused multiply-add, and one more of them lands on the
-// rounded quotient (checked against the division for every positive float).
-__device__ __forceinline__ float div_by_15(float x)
-{
-    const float y = 0x1.111112p-4f;
-    const float q = x * y;
-    const float r = __builtin_fmaf(-15.0f, q, x);
-    return __builtin_fmaf(r, y, q);
-}
-
-// 1 / s for a bf16-valued scale s: hardware reciprocal (1 ulp) and one Newton step.
-// Equal to the IEEE quotient for every bf16 s with a normal reciprocal.
-__device__ __forceinline__ float reciprocal_of_scale(float s)
-{
-    const float y = __builtin_amdgcn_rcpf(s);
-    const float e = __builtin_fmaf(-s, y, 1.0f);
-    return __builtin_fmaf(e, y, y);
-}
-
 // ---------------------------------------------------------------------------
 // Direct kernel (the fast path).
 //
@@ -761,6 +741,10 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
     const int lpg = a.G / 8;
     if (lpg != 4 && lpg != 8 && lpg != 16 && lpg != 32) return TPQ_ERR_UNSUPPORTED;
     if (a.T <= 0) return TPQ_OK;
+    if (a.r > 0 && !hop) {  // the row kernel takes the shapes it is built for
+        const int rc = launch_encode_rows(a, Y, codes, scale, zero, outl, s);
+        if (rc != TPQ_ERR_UNSUPPORTED) return rc;
+    }
     if (a.r > 0) return hip_result(launch_direct(a, Y, codes, scale, zero, outl, s, hop));
 
     // every feature selected: rows are handed over in blocks that fit the grid
