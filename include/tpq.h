@@ -78,9 +78,9 @@ extern "C" {
 
 #define TPQ_ACC_FP32 0 /* x_0 + x_1 + ... in fp32, ascending device order              */
 #define TPQ_ACC_BF16 1 /* every term and every partial sum rounded to bf16             */
-#define TPQ_ACC_FAST 2 /* sum of code*scale by fp32 fused multiply-add plus the sum of the
-                        * zeros, rounded once: not bit-identical to either chain, within
-                        * 1e-2 * sum_i |x_hat_i| of both (the tolerance of the bf16 chain)    */
+#define TPQ_ACC_FAST 2 /* the bf16 accumulate mode at its tolerance instead of its letter: terms
+                        * and partial sums stay fp32, one rounding at the end (the arithmetic
+                        * of TPQ_ACC_FP32); within 1e-2 * sum_i |x_hat_i| of the bf16 chain   */
 #define TPQ_OUT_BF16 0
 #define TPQ_OUT_FP32 1
 

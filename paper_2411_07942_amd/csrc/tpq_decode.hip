@@ -618,12 +618,7 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
                   const RankPtrs &zero_in, const RankPtrs &outl_in, int accum, int out_dtype,
                   hipStream_t s)
 {
-    // the row kernel takes the shapes it is built for; everything else runs below
-    {
-        const int rc = launch_decode_rows(a_in, codes_in, scale_in, zero_in, outl_in, accum, out_dtype, s);
-        if (rc != TPQ_ERR_UNSUPPORTED) return rc;
-    }
-    // (here TPQ_ACC_FAST is evaluated as the fp32 chain, which is within its tolerance)
+    // TPQ_ACC_FAST is evaluated as the fp32 chain (one final rounding), which is within its tolerance
     if (accum == TPQ_ACC_FAST) accum = TPQ_ACC_FP32;
     const int lpg = a_in.G / 8;
     const int tasks = a_in.chunks_padded / 64 + (a_in.k + 63) / 64;  // waves per row

@@ -89,16 +89,18 @@ __device__ __forceinline__ float dpp_f32(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
-// min and max over aligned groups of LPG lanes (LPG in {4, 8, 16, 32}); every lane
+// min and max over aligned groups of LPG lanes (LPG in {2, 4, 8, 16, 32}); every lane
 // of the group ends up with the group's result.
 template <int LPG>
 __device__ __forceinline__ void group_minmax(float &mn, float &mx)
 {
-    static_assert(LPG == 4 || LPG == 8 || LPG == 16 || LPG == 32, "lanes per group");
+    static_assert(LPG == 2 || LPG == 4 || LPG == 8 || LPG == 16 || LPG == 32, "lanes per group");
     mn = fminf(mn, dpp_f32<0xB1>(mn));
     mx = fmaxf(mx, dpp_f32<0xB1>(mx));
-    mn = fminf(mn, dpp_f32<0x4E>(mn));
-    mx = fmaxf(mx, dpp_f32<0x4E>(mx));
+    if (LPG >= 4) {
+        mn = fminf(mn, dpp_f32<0x4E>(mn));
+        mx = fmaxf(mx, dpp_f32<0x4E>(mx));
+    }
     if (LPG == 8) {
         mn = fminf(mn, dpp_f32<0x141>(mn));
         mx = fmaxf(mx, dpp_f32<0x141>(mx));

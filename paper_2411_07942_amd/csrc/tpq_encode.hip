@@ -598,7 +598,7 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     // The segment's codes are one contiguous piece of the row (256 bytes per pass).  They leave
     // as 128-bit stores: every lane parks its P words in LDS in chunk order and takes four
     // consecutive ones back -- 1 KB per store instruction instead of 256 bytes, which the
-    // memory system takes markedly better (tests/probes/stream_probe: "16-byte stores").
+    // memory system takes markedly better in a bare streaming kernel.
     // A last segment's final one to three words go out singly, so that nothing past the
     // row's codes is written.
     {
@@ -741,10 +741,6 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
     const int lpg = a.G / 8;
     if (lpg != 4 && lpg != 8 && lpg != 16 && lpg != 32) return TPQ_ERR_UNSUPPORTED;
     if (a.T <= 0) return TPQ_OK;
-    if (a.r > 0 && !hop) {  // the row kernel takes the shapes it is built for
-        const int rc = launch_encode_rows(a, Y, codes, scale, zero, outl, s);
-        if (rc != TPQ_ERR_UNSUPPORTED) return rc;
-    }
     if (a.r > 0) return hip_result(launch_direct(a, Y, codes, scale, zero, outl, s, hop));
 
     // every feature selected: rows are handed over in blocks that fit the grid

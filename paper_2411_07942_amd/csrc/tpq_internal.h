@@ -294,14 +294,6 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
 int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
                   const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
                   hipStream_t s);
-// the row kernel of encode; TPQ_ERR_UNSUPPORTED (and nothing launched) for shapes it does not take
-int launch_encode_rows(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
-                       const RankPtrs &scale, const RankPtrs &zero, const RankPtrs &outl,
-                       hipStream_t s);
-// the row kernel of decode_reduce; TPQ_ERR_UNSUPPORTED (and nothing launched) for shapes it does not take
-int launch_decode_rows(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
-                       const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
-                       hipStream_t s);
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
                          float gamma, float *m, float *M, float *ws, hipStream_t s);
 int calibrate_parts(int64_t S, int E);

@@ -145,7 +145,7 @@ def test_decode_argument_errors():
         a = dict(ok, **kw)
         return lib.tpq_decode_reduce(LP, a["plan"], a["n"], a["T"], a["c"], a["s"], a["z"], a["o"],
                                      a["acc"], a["od"], a["out"], a["ld"], None)
-    assert call(acc=2) == tpq.ERR_UNSUPPORTED
+    assert call(acc=3) == tpq.ERR_UNSUPPORTED  # 0, 1, 2 are the modes
     assert call(od=3) == tpq.ERR_UNSUPPORTED
     assert call(out=None) == tpq.ERR_NULL
     assert call(out=_fake(0x90004)) == tpq.ERR_ALIGN
