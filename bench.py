@@ -188,7 +188,7 @@ def main():
     n_seq, S = wl.n_cal_sequences(w), w.cal_seq
     m = torch.zeros((N, E), device=dev)
     M = torch.zeros((N, E), device=dev)
-    ws = torch.empty(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device=dev)
     for i in range(N):
         for s in range(n_seq):
             tpq.calibrate(wl.calibration_sequence(w, 0, i, s, device=dev), i, N, s, 0.01, m, M, ws)
@@ -312,7 +312,7 @@ def main():
     pool = [wl.calibration_sequence(wc, 0, 0, s, device=dev) for s in range(args.calibrate_chunks)]
     mc = torch.zeros((1, Ec), device=dev)
     Mc = torch.zeros((1, Ec), device=dev)
-    wsc = torch.empty(tpq.calibrate_workspace_bytes(Sc, Ec), dtype=torch.uint8, device=dev)
+    wsc = torch.zeros(tpq.calibrate_workspace_bytes(Sc, Ec), dtype=torch.uint8, device=dev)
     for s in range(len(pool)):
         tpq.calibrate(pool[s], 0, 1, s, 0.01, mc, Mc, wsc)
     torch.cuda.synchronize()

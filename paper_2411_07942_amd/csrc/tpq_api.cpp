@@ -156,7 +156,7 @@ int tpq_plan_check(const tpq_layout *L, const void *plan, void *stream)
 size_t tpq_calibrate_workspace_bytes(int64_t S, int E)
 {
     if (S < 0 || E < 8 || E > TPQ_MAX_E || (E % 8)) return 0;
-    return static_cast<size_t>(calibrate_parts(S, E)) * 2u * static_cast<size_t>(E) * sizeof(float);
+    return calibrate_workspace_bytes(E);
 }
 
 int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank, int n_ranks,
@@ -176,7 +176,7 @@ int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank, in
     return launch_colminmax_ema(Y, S, ldY, E, seq_index == 0, gamma,
                                 m + static_cast<int64_t>(rank) * E,
                                 M + static_cast<int64_t>(rank) * E,
-                                static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+                                workspace, kCalMaxParts, static_cast<hipStream_t>(stream));
 }
 
 size_t tpq_calibrate_finalize_workspace_bytes(int E)

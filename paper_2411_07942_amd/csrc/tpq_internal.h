@@ -294,9 +294,13 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
 int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
                   const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
                   hipStream_t s);
+// calibration workspace: arrival counters (zero between calls), then up to kCalMaxParts slices
+// of partial minima / maxima
+constexpr int kCalMaxParts = 128;
+size_t calibrate_workspace_bytes(int E);
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
-                         float gamma, float *m, float *M, float *ws, hipStream_t s);
-int calibrate_parts(int64_t S, int E);
+                         float gamma, float *m, float *M, void *ws, int max_parts, hipStream_t s);
+int calibrate_parts(int64_t S, int E, int compute_units, int max_parts);
 int launch_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
                          int n_ranks, float *step, float *inv, hipStream_t s);
 int launch_finalize(const float *m, const float *M, int N, int E, int k, float *R,

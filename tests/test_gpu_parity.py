@@ -291,7 +291,7 @@ def _calibrate_both(w, n_seq, S, block=0, N=None, gamma=0.01, ld_pad=0):
     E = w.E
     m = torch.full((N, E), 9.0, device="cuda")
     M = torch.full((N, E), -9.0, device="cuda")
-    ws = torch.empty(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
     m_ref = np.zeros((N, E), np.float32)
     M_ref = np.zeros((N, E), np.float32)
     for i in range(N):
@@ -369,7 +369,7 @@ def test_calibration_config_reduced_stream_and_resume():
         assert set(cols.tolist()) <= set(idx.cpu().tolist())
     # resume
     S, N, E = 4096, 1, w.E
-    ws = torch.empty(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
     seqs = [wl.calibration_sequence(w, 3, 0, s, device="cuda", S=S) for s in range(6)]
     mA, MA = torch.zeros((N, E), device="cuda"), torch.zeros((N, E), device="cuda")
     for s, Y in enumerate(seqs):

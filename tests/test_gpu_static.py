@@ -249,7 +249,7 @@ def test_calibrated_static_end_to_end():
     m = torch.empty((N, E), device="cuda")
     M = torch.empty((N, E), device="cuda")
     S = w.cal_seq
-    ws = torch.empty(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(tpq.calibrate_workspace_bytes(S, E), dtype=torch.uint8, device="cuda")
     m_ref = np.zeros((N, E), np.float32)
     M_ref = np.zeros((N, E), np.float32)
     for i in range(N):
