@@ -149,12 +149,8 @@ int tpq_plan_check(const tpq_layout *L, const void *plan, void *stream);
  *   otherwise:       m = (1-gamma)*m + gamma*cmin  (three rounded fp32 ops), same for M
  *   Y         [device] bf16 [S][ldY], ldY in elements, multiple of 8, >= E
  *   m, M      [device] fp32 [n_ranks][E]; row `rank` is updated
- *   workspace [device] >= tpq_calibrate_workspace_bytes(S, E) bytes, 16-byte aligned.  Its
- *             first 256 bytes hold arrival counters of the kernel's workgroups: the caller
- *             zero-fills them once after allocating (hipMemset; a zero-filled allocation does),
- *             every call leaves them zero again.  Calls that share a workspace must not
- *             overlap in time (the same stream, or ordered by events).  A call that is
- *             aborted half-way (device reset) leaves the counters undefined: zero them again. */
+ *   workspace [device] >= tpq_calibrate_workspace_bytes(S, E) bytes, 16-byte aligned, contents
+ *             arbitrary; calls that share a workspace must not overlap in time */
 size_t tpq_calibrate_workspace_bytes(int64_t S, int E);
 int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank,
                   int n_ranks, int64_t seq_index, float gamma, float *m, float *M,

@@ -171,8 +171,7 @@ def calibrate_workspace_bytes(S: int, E: int) -> int:
 
 def calibrate(Y: torch.Tensor, rank: int, n_ranks: int, seq_index: int, gamma: float,
               m: torch.Tensor, M: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
-    """One sequence Y (bf16 [S,E], row stride Y.stride(0)) of device `rank`; m, M fp32 [n_ranks,E].
-    workspace: zero-filled once before its first use (calibrate_workspace() makes one)."""
+    """One sequence Y (bf16 [S,E], row stride Y.stride(0)) of device `rank`; m, M fp32 [n_ranks,E]."""
     S, E = Y.shape
     _check(_load().tpq_calibrate(_ptr(Y), S, Y.stride(0) if S > 1 else max(E, Y.stride(0)), E,
                                  rank, n_ranks, seq_index, gamma, _ptr(m), _ptr(M),
@@ -181,8 +180,8 @@ def calibrate(Y: torch.Tensor, rank: int, n_ranks: int, seq_index: int, gamma: f
 
 
 def calibrate_workspace(S: int, E: int, device) -> torch.Tensor:
-    """A workspace for calibrate(), zero-filled as its arrival counters must be at first use."""
-    return torch.zeros(max(calibrate_workspace_bytes(S, E), 16), dtype=torch.uint8, device=device)
+    """A workspace for calibrate()."""
+    return torch.empty(max(calibrate_workspace_bytes(S, E), 16), dtype=torch.uint8, device=device)
 
 
 def calibrate_finalize_workspace_bytes(E: int) -> int:

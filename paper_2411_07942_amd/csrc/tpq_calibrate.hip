@@ -1,6 +1,8 @@
 // tpq_calibrate kernels: per-feature min / max of a calibration sequence, the
 // moving-average update of Eq. (1), (2), and the final range aggregation and top-k
 // selection (paper Sec. 3).
+#include <atomic>
+
 #include "tpq_device.h"
 #include "tpq_internal.h"
 
@@ -10,25 +12,21 @@ constexpr int kStripLanes = 64;        // lanes across columns; 8 columns per la
 constexpr int kStripCols = 8 * kStripLanes;
 constexpr int kWavesPerBlock = 8;      // waves of a block share columns, split rows
 constexpr int kUnroll = 8;             // rows in flight per lane
-// Workspace: kCalCounters 32-bit arrival counters (one per column strip; zero between calls),
-// then the partial minima / maxima as [part][0 = min, 1 = max][E] floats.
-constexpr int kCalCounters = TPQ_MAX_E / kStripCols;  // 64
-constexpr size_t kCalCounterBytes = 256;
-static_assert(kCalCounters * 4 <= kCalCounterBytes, "counters fit their area");
-
+// Workspace: the partial minima / maxima as [part][0 = min, 1 = max][E] floats.
 size_t calibrate_workspace_bytes(int E)
 {
-    return kCalCounterBytes + static_cast<size_t>(kCalMaxParts) * 2u * static_cast<size_t>(E) * sizeof(float);
+    return static_cast<size_t>(kCalMaxParts) * 2u * static_cast<size_t>(E) * sizeof(float);
 }
 
 // How many row slices ("parts") a sequence of S rows is cut into.  Each (column strip,
-// part) is one workgroup of 8 waves; two such workgroups per compute unit keep the whole
-// machine reading with nothing left over for a second round, which a partly filled round
-// would make as long as a full one.
+// part) is one workgroup of 8 waves with 8 rows of loads in flight per wave; one such
+// workgroup per compute unit reads fastest on this part (measured: two per unit 8 % slower,
+// three and four slower still), and nothing is left over for a second round, which a partly
+// filled round would make as long as a full one.
 int calibrate_parts(int64_t S, int E, int compute_units, int max_parts)
 {
     const int strips = (E + kStripCols - 1) / kStripCols;
-    int64_t parts = (2 * static_cast<int64_t>(compute_units)) / strips;
+    int64_t parts = static_cast<int64_t>(compute_units) / strips;
     // at least one row per wave and unrolled step where S allows
     if (parts > S / (kWavesPerBlock * kUnroll)) parts = S / (kWavesPerBlock * kUnroll);
     if (parts > max_parts) parts = max_parts;
@@ -38,21 +36,15 @@ int calibrate_parts(int64_t S, int E, int compute_units, int max_parts)
 
 typedef unsigned int u32x4_cal __attribute__((ext_vector_type(4)));
 
-// Column min / max over one slice of rows, and -- in the workgroup that finishes a strip
-// last -- the moving-average update of Eq. (1), (2) for the strip's features.
-// Lane l of every wave owns columns 8*(64*blockIdx.x + l) .. +7 and keeps 8 running minima
-// and maxima in registers; the block's waves take interleaved rows, kUnroll 128-bit loads in
-// flight each, and are combined through LDS.  The upper bf16 of a word is compared as the
-// whole word (it orders like the value itself; the low half is masked off at the end).
-// Partials go to `partial` as [part][0 = min, 1 = max][E]; then the workgroup takes a ticket
-// from its strip's counter, and the one that draws the last ticket reads the strip's partials
-// back (they are in memory: every workgroup fenced before its ticket), applies the update and
-// leaves the counter at zero for the next call.  Minimum and maximum are exact and
-// order-free, so the result does not depend on which workgroup comes last.
-__global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax_ema(
-    const uint16_t *__restrict__ Y, int64_t S, int64_t ldY, int E, int rows_per_part, int parts,
-    uint32_t *__restrict__ counters, float *__restrict__ partial, int first, float gamma,
-    float *__restrict__ m, float *__restrict__ M)
+// Column min / max over one slice of rows.  Lane l of every wave owns columns
+// 8*(64*blockIdx.x + l) .. +7 and keeps 8 running minima and maxima in registers;
+// the block's waves take interleaved rows, kUnroll 128-bit loads in flight each,
+// and are combined through LDS.  The upper bf16 of a word is compared as the whole
+// word (it orders like the value itself; the low half is masked off at the end).
+// Partials go to `partial` as [part][0 = min, 1 = max][E].
+__global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax(
+    const uint16_t *__restrict__ Y, int64_t S, int64_t ldY, int E, int rows_per_part,
+    float *__restrict__ partial)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -101,7 +93,6 @@ __global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax_ema(
     }
 
     __shared__ float red[kWavesPerBlock][2][8][kStripLanes];
-    __shared__ uint32_t ticket;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         red[wave][0][e][lane] = mn[e];
@@ -121,56 +112,88 @@ __global__ __launch_bounds__(kStripLanes *kWavesPerBlock) void k_colminmax_ema(
         partial[(static_cast<int64_t>(blockIdx.y) * 2 + 0) * E + j] = a;
         partial[(static_cast<int64_t>(blockIdx.y) * 2 + 1) * E + j] = b;
     }
-    // the partials are in memory before the ticket is drawn ...
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) ticket = atomicAdd(&counters[blockIdx.x], 1u);
-    __syncthreads();
-    if (ticket != static_cast<uint32_t>(parts) - 1u) return;
-    // ... and the last workgroup of the strip sees every other one's
-    __threadfence();
-    if (live) {
-        float cmin = 3.4028235e38f, cmax = -3.4028235e38f;
-        for (int p = 0; p < parts; ++p) {
-            cmin = fminf(cmin, __hip_atomic_load(&partial[(2 * static_cast<int64_t>(p)) * E + j], __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT));
-            cmax = fmaxf(cmax, __hip_atomic_load(&partial[(2 * static_cast<int64_t>(p) + 1) * E + j],
-                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        }
-        cmin += 0.0f;  // a zero is taken as +0
-        cmax += 0.0f;
-        if (first) {
-            m[j] = cmin;
-            M[j] = cmax;
-        } else {
-            const float keep = 1.0f - gamma;
-            float x = keep * m[j];
-            float y = gamma * cmin;
-            m[j] = x + y;
-            x = keep * M[j];
-            y = gamma * cmax;
-            M[j] = x + y;
+}
+
+// Combine the parts and apply Eq. (1), (2) to one device's state.  A block owns 64
+// features; its 4 waves take interleaved parts and are combined through LDS.
+__global__ __launch_bounds__(256) void k_ema(const float *__restrict__ partial, int parts, int E,
+                                             int first, float gamma, float *__restrict__ m,
+                                             float *__restrict__ M)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + lane;
+    float cmin = 3.4028235e38f, cmax = -3.4028235e38f;
+    if (j < E) {
+        for (int p = wave; p < parts; p += 4) {
+            cmin = fminf(cmin, partial[(2 * static_cast<int64_t>(p)) * E + j]);
+            cmax = fmaxf(cmax, partial[(2 * static_cast<int64_t>(p) + 1) * E + j]);
         }
     }
-    if (threadIdx.x == 0) counters[blockIdx.x] = 0u;  // ready for the next call
+    __shared__ float red[4][2][64];
+    red[wave][0][lane] = cmin;
+    red[wave][1][lane] = cmax;
+    __syncthreads();
+    if (wave != 0 || j >= E) return;
+#pragma unroll
+    for (int w2 = 1; w2 < 4; ++w2) {
+        cmin = fminf(cmin, red[w2][0][lane]);
+        cmax = fmaxf(cmax, red[w2][1][lane]);
+    }
+    cmin += 0.0f;  // a zero is taken as +0
+    cmax += 0.0f;
+    if (first) {
+        m[j] = cmin;
+        M[j] = cmax;
+    } else {
+        const float keep = 1.0f - gamma;
+        float x = keep * m[j];
+        float y = gamma * cmin;
+        m[j] = x + y;
+        x = keep * M[j];
+        y = gamma * cmax;
+        M[j] = x + y;
+    }
+}
+
+// The number of compute units of the current device (looked up once per device: the query is
+// slow compared with a launch).
+static hipError_t compute_units_of_current_device(int *out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> known[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < kMaxDevices) {
+        const int c = known[dev].load(std::memory_order_relaxed);
+        if (c > 0) {
+            *out = c;
+            return hipSuccess;
+        }
+    }
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if (cus < 1) cus = 1;
+    if (dev >= 0 && dev < kMaxDevices) known[dev].store(cus, std::memory_order_relaxed);
+    *out = cus;
+    return hipSuccess;
 }
 
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
                          float gamma, float *m, float *M, void *ws, int max_parts, hipStream_t s)
 {
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return hip_result(e);
+    int cus = 0;
+    const hipError_t e0 = compute_units_of_current_device(&cus);
+    if (e0 != hipSuccess) return hip_result(e0);
     const int parts = calibrate_parts(S, E, cus, max_parts);
     const int rows_per_part = static_cast<int>((S + parts - 1) / parts);
     // the last parts may be empty when S is not a multiple; recompute the live count
     const int live_parts = static_cast<int>((S + rows_per_part - 1) / rows_per_part);
     const dim3 grid((E + kStripCols - 1) / kStripCols, live_parts);
-    uint32_t *counters = static_cast<uint32_t *>(ws);
-    float *partial = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + kCalCounterBytes);
-    k_colminmax_ema<<<grid, kStripLanes * kWavesPerBlock, 0, s>>>(Y, S, ldY, E, rows_per_part, live_parts, counters,
-                                                                   partial, first, gamma, m, M);
+    float *partial = static_cast<float *>(ws);
+    k_colminmax<<<grid, kStripLanes * kWavesPerBlock, 0, s>>>(Y, S, ldY, E, rows_per_part, partial);
+    k_ema<<<(E + 63) / 64, 256, 0, s>>>(partial, live_parts, E, first, gamma, m, M);
     return hip_result(hipGetLastError());
 }
 

@@ -294,8 +294,7 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
 int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
                   const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
                   hipStream_t s);
-// calibration workspace: arrival counters (zero between calls), then up to kCalMaxParts slices
-// of partial minima / maxima
+// calibration workspace: up to kCalMaxParts slices of partial minima / maxima
 constexpr int kCalMaxParts = 128;
 size_t calibrate_workspace_bytes(int E);
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
