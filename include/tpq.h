@@ -156,6 +156,20 @@ int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank,
                   int n_ranks, int64_t seq_index, float gamma, float *m, float *M,
                   void *workspace, size_t ws_bytes, void *stream);
 
+/* tpq_calibrate for callers that cannot provide scratch memory they have allocated (code
+ * under HIP graph capture, serving loops or harnesses that forbid hipMalloc): the same
+ * kernels, with the partial minima / maxima of the row slices in a buffer that is part
+ * of the library's device image (TPQ_CALIBRATE_FIXED_SCRATCH_BYTES per GPU, held until the
+ * process ends) instead of a workspace argument.  Allocates nothing and calls no allocating
+ * routine.  E <= TPQ_CALIBRATE_FIXED_MAX_E (TPQ_ERR_SHAPE beyond that); everything else as
+ * tpq_calibrate, results bit-identical to it.  Every call on a GPU uses that GPU's one
+ * buffer: calls that overlap in time on one GPU race (order them on one stream or by events). */
+#define TPQ_CALIBRATE_FIXED_MAX_E 8192
+#define TPQ_CALIBRATE_FIXED_SCRATCH_BYTES (64 * 2 * TPQ_CALIBRATE_FIXED_MAX_E * 4)
+int tpq_calibrate_fixed(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank,
+                        int n_ranks, int64_t seq_index, float gamma, float *m, float *M,
+                        void *stream);
+
 /* After the last sequence (Sec. 3):
  *   R[i][j] = 2*max(-m[i][j], M[i][j]);  Rbar[j] = R[0][j] + R[1][j] + ... (fp32, ascending i)
  *   the k features with the largest Rbar (ties: lower index first)

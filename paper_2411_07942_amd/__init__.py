@@ -31,7 +31,7 @@ EXPORTS = [
     "tpq_layout_init", "tpq_payload_bits", "tpq_wire_bits", "tpq_strerror", "tpq_last_hip_error",
     "tpq_time_next_launch",
     "tpq_plan_bytes", "tpq_plan_build", "tpq_plan_check",
-    "tpq_calibrate_workspace_bytes", "tpq_calibrate",
+    "tpq_calibrate_workspace_bytes", "tpq_calibrate", "tpq_calibrate_fixed",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
     "tpq_encode", "tpq_hop", "tpq_decode_reduce", "tpq_decode_reduce_fused",
     "tpq_static_table_floats", "tpq_static_params", "tpq_encode_static", "tpq_decode_reduce_static",
@@ -85,6 +85,7 @@ def _load():
     lib.tpq_calibrate_workspace_bytes.restype = sz
     lib.tpq_calibrate.argtypes = [vp, i64, i64, c_int, c_int, c_int, i64, ctypes.c_float,
                                   vp, vp, vp, sz, vp]
+    lib.tpq_calibrate_fixed.argtypes = [vp, i64, i64, c_int, c_int, c_int, i64, ctypes.c_float, vp, vp, vp]
     lib.tpq_calibrate_finalize_workspace_bytes.argtypes = [c_int]
     lib.tpq_calibrate_finalize_workspace_bytes.restype = sz
     lib.tpq_calibrate_finalize.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]
@@ -182,6 +183,15 @@ def calibrate(Y: torch.Tensor, rank: int, n_ranks: int, seq_index: int, gamma: f
 def calibrate_workspace(S: int, E: int, device) -> torch.Tensor:
     """A workspace for calibrate()."""
     return torch.empty(max(calibrate_workspace_bytes(S, E), 16), dtype=torch.uint8, device=device)
+
+
+def calibrate_fixed(Y: torch.Tensor, rank: int, n_ranks: int, seq_index: int, gamma: float,
+                    m: torch.Tensor, M: torch.Tensor, stream=None) -> None:
+    """calibrate() with the library's own scratch buffer instead of a workspace (tpq_calibrate_fixed)."""
+    S, E = Y.shape
+    _check(_load().tpq_calibrate_fixed(_ptr(Y), S, Y.stride(0) if S > 1 else max(E, Y.stride(0)), E,
+                                       rank, n_ranks, seq_index, gamma, _ptr(m), _ptr(M),
+                                       _stream(stream)), "tpq_calibrate_fixed")
 
 
 def calibrate_finalize_workspace_bytes(E: int) -> int:

@@ -179,6 +179,27 @@ int tpq_calibrate(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank, in
                                 workspace, kCalMaxParts, static_cast<hipStream_t>(stream));
 }
 
+int tpq_calibrate_fixed(const uint16_t *Y, int64_t S, int64_t ldY, int E, int rank, int n_ranks,
+                        int64_t seq_index, float gamma, float *m, float *M, void *stream)
+{
+    if (E < 8 || E > TPQ_CALIBRATE_FIXED_MAX_E || (E % 8) != 0 || S < 0 || ldY < E || n_ranks < 1 ||
+        n_ranks > TPQ_MAX_RANKS || rank < 0 || rank >= n_ranks || seq_index < 0)
+        return TPQ_ERR_SHAPE;
+    if (!(gamma >= 0.0f && gamma <= 1.0f)) return TPQ_ERR_SHAPE;
+    if (S == 0) return TPQ_OK;
+    if (!Y || !m || !M) return TPQ_ERR_NULL;
+    if ((ldY % 8) != 0 || !aligned16(Y) || (reinterpret_cast<uintptr_t>(m) & 3u) ||
+        (reinterpret_cast<uintptr_t>(M) & 3u))
+        return TPQ_ERR_ALIGN;
+    void *scratch = nullptr;
+    const int rc = calibrate_fixed_scratch(&scratch);
+    if (rc) return rc;
+    return launch_colminmax_ema(Y, S, ldY, E, seq_index == 0, gamma,
+                                m + static_cast<int64_t>(rank) * E,
+                                M + static_cast<int64_t>(rank) * E, scratch, kCalFixedMaxParts,
+                                static_cast<hipStream_t>(stream));
+}
+
 size_t tpq_calibrate_finalize_workspace_bytes(int E)
 {
     if (E < 8 || E > TPQ_MAX_E || (E % 8)) return 0;

@@ -2,6 +2,7 @@
 // moving-average update of Eq. (1), (2), and the final range aggregation and top-k
 // selection (paper Sec. 3).
 #include <atomic>
+#include <mutex>
 
 #include "tpq_device.h"
 #include "tpq_internal.h"
@@ -195,6 +196,36 @@ int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int f
     k_colminmax<<<grid, kStripLanes * kWavesPerBlock, 0, s>>>(Y, S, ldY, E, rows_per_part, partial);
     k_ema<<<(E + 63) / 64, 256, 0, s>>>(partial, live_parts, E, first, gamma, m, M);
     return hip_result(hipGetLastError());
+}
+
+// ---- scratch of tpq_calibrate_fixed ------------------------------------------------
+// The partials for callers that cannot bring a workspace: part of the device image, so every
+// GPU the library runs on holds its own copy.  Nothing in it has to start at zero: a call
+// writes every partial that it reads.  In host code the array's name is only a handle: the
+// device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[TPQ_CALIBRATE_FIXED_SCRATCH_BYTES];
+static_assert(TPQ_CALIBRATE_FIXED_SCRATCH_BYTES ==
+                  static_cast<size_t>(kCalFixedMaxParts) * 2u * TPQ_CALIBRATE_FIXED_MAX_E * sizeof(float),
+              "scratch holds kCalFixedMaxParts slices of partials at the largest E");
+
+int calibrate_fixed_scratch(void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_result(e);
+    if (dev < 0 || dev >= kMaxDevices) return TPQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_result(e);
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return TPQ_OK;
 }
 
 // ---- finalize -------------------------------------------------------------------

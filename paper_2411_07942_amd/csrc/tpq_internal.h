@@ -300,6 +300,9 @@ size_t calibrate_workspace_bytes(int E);
 int launch_colminmax_ema(const uint16_t *Y, int64_t S, int64_t ldY, int E, int first,
                          float gamma, float *m, float *M, void *ws, int max_parts, hipStream_t s);
 int calibrate_parts(int64_t S, int E, int compute_units, int max_parts);
+// the library's own scratch for tpq_calibrate_fixed: its device address on the current GPU
+constexpr int kCalFixedMaxParts = 64;
+int calibrate_fixed_scratch(void **ptr);
 int launch_static_params(const tpq_layout *L, const void *plan, const float *m, const float *M,
                          int n_ranks, float *step, float *inv, hipStream_t s);
 int launch_finalize(const float *m, const float *M, int N, int E, int k, float *R,
