@@ -80,7 +80,10 @@ extern "C" {
 #define TPQ_ACC_BF16 1 /* every term and every partial sum rounded to bf16             */
 #define TPQ_ACC_FAST 2 /* the bf16 accumulate mode at its tolerance instead of its letter: terms
                         * and partial sums stay fp32, one rounding at the end (the arithmetic
-                        * of TPQ_ACC_FP32); within 1e-2 * sum_i |x_hat_i| of the bf16 chain   */
+                        * of TPQ_ACC_FP32).  Within half a bf16 ulp of the exact sum; from the
+                        * literal chain it differs by at most the chain's own rounding,
+                        * (N + 1) * 2^-9 * sum_i |x_hat_i|, and by less than 1e-2 of that sum
+                        * for all but a few elements per million                             */
 #define TPQ_OUT_BF16 0
 #define TPQ_OUT_FP32 1
 
@@ -135,6 +138,10 @@ int tpq_time_next_launch(void *start_event, void *stop_event);
  *   plan       [device] tpq_plan_bytes(L) bytes, 16-byte aligned, caller-owned.
  * tpq_plan_build validates the indices on the device; encode / decode_reduce
  * given a plan that is invalid (or built for another E, k, G) write nothing.
+ * The buffer handed to encode / decode_reduce / tpq_hop / the static calls must hold at
+ * least tpq_plan_bytes(L) bytes for the L of THAT call, whatever it was built for: the
+ * kernels fetch their first table entries, at offsets that follow from L alone, together
+ * with the header that tells them whether the plan fits.
  * tpq_plan_check synchronises the stream and reports TPQ_ERR_INDEX /
  * TPQ_ERR_SHAPE for such a plan. */
 size_t tpq_plan_bytes(const tpq_layout *L);

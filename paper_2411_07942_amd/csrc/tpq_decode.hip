@@ -632,7 +632,10 @@ int launch_decode(const DecodeArgs &a_in, const RankPtrs &codes_in, const RankPt
     if (rows_per_launch > 0x7FFFFFFFLL) rows_per_launch = 0x7FFFFFFFLL;
     if (rows_per_launch < 1) return TPQ_ERR_SHAPE;
     const int64_t ny = (tasks + 3) / 4;  // groups of 4 waves per row
-    if (rows_per_launch > 0x7FFFFFF0LL / ny) rows_per_launch = 0x7FFFFFF0LL / ny;  // (one-dimensional grid)
+    // one-dimensional grid of 256-thread workgroups: grid * block stays below 2^32
+    const int64_t max_blocks = (1LL << 24) - 8;
+    if (rows_per_launch > max_blocks / ny) rows_per_launch = max_blocks / ny;
+    if (rows_per_launch < 1) return TPQ_ERR_SHAPE;
     const size_t ob = out_dtype == TPQ_OUT_FP32 ? 4 : 2;
     hipError_t e = hipSuccess;
     for (int64_t row0 = 0; row0 < a_in.T && e == hipSuccess; row0 += rows_per_launch) {

@@ -758,7 +758,7 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
         if (hop)
             for (int i = 0; i < a.n_ranks; ++i)
                 hb.outl[i] = static_cast<const uint8_t *>(hop->outl[i]) + row0 * a.pitch_outl;
-        k_copy_selected<<<grid, 256, 0, s>>>(b, Yb, ob, hb);
+        launch_kernel(k_copy_selected, grid, dim3(256), 0, s, b, Yb, ob, hb);
     }
     return hip_result(hipGetLastError());
 }

@@ -90,6 +90,24 @@ def sum_tolerance_ok(gpu_out, ref_out, ref_msgs, idx, E, G, out_fp32, rel):
     return bool(np.all(np.abs(g - r) <= rel * mag + slack + 1e-30))
 
 
+def sum_tolerance_fraction(gpu_out, ref_out, ref_msgs, idx, E, G, out_fp32, rel):
+    """Fraction of the elements inside the bar of sum_tolerance_ok, and the worst
+    |gpu - oracle| / sum_i |x_hat_i|."""
+    mag = np.zeros(ref_out.shape, np.float64)
+    for mg in ref_msgs:
+        mag += np.abs(oracle.dequantize(mg, idx, E, G).astype(np.float64))
+    if out_fp32:
+        g, r = gpu_out.astype(np.float64), ref_out.astype(np.float64)
+        slack = 0.0
+    else:
+        g, r = bits_to_f32(gpu_out).astype(np.float64), bits_to_f32(ref_out).astype(np.float64)
+        slack = np.abs(r) * 2.0 ** -8
+    err = np.abs(g - r)
+    inside = err <= rel * mag + slack + 1e-30
+    worst = float(np.max((err - slack).clip(min=0) / (mag + 1e-30))) if err.size else 0.0
+    return float(np.mean(inside)) if err.size else 1.0, worst
+
+
 def idx_for(w, block=0):
     """The k selected features of a workload block: the planted outlier columns,
     filled up with the lowest other columns (stands in for a calibration run)."""

@@ -111,9 +111,7 @@ def test_llama_prefill_full_size():
     w = wl.LLAMA_PREFILL
     Ys = wl.partial_sums(w, device="cuda")
     _, addend, bias = _inputs(w.E, w.T, 1, 11)
-    rng = np.random.default_rng(5)
-    rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 13, replace=False)])
-    _case(w.E, w.G, Ys, idx_for(w), addend, bias, rows=rows)
+    _case(w.E, w.G, Ys, idx_for(w), addend, bias)
 
 
 def test_argument_errors():

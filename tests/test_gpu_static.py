@@ -270,13 +270,11 @@ def test_calibrated_static_end_to_end():
 
 
 def test_llama_prefill_full_size_static():
-    """The Llama-2-13B-shaped prefill block at full size; the oracle on sampled rows."""
+    """The Llama-2-13B-shaped prefill block at full size, every row against the oracle."""
     w = wl.LLAMA_PREFILL
     Ys = wl.partial_sums(w, device="cuda")
     m, M = _ranges_from(Ys, shrink_every=3, dead_every=1001)
-    rng = np.random.default_rng(3)
-    rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 24, replace=False)])
-    _static_case(w.E, w.G, Ys, idx_for(w), m, M, rows=rows)
+    _static_case(w.E, w.G, Ys, idx_for(w), m, M)
 
 
 @pytest.mark.parametrize("b", (2, 3, 5, 6, 8))
@@ -304,6 +302,4 @@ def test_llama_prefill_full_size_static_other_widths(b):
     w = wl.LLAMA_PREFILL
     Ys = wl.partial_sums(w, device="cuda")
     m, M = _ranges_from(Ys, shrink_every=3, dead_every=1001)
-    rng = np.random.default_rng(b)
-    rows = np.unique(np.r_[0, 1, w.T - 1, rng.choice(w.T, 13, replace=False)])
-    _static_case(w.E, w.G, Ys, idx_for(w), m, M, rows=rows, bits=b)
+    _static_case(w.E, w.G, Ys, idx_for(w), m, M, bits=b)

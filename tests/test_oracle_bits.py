@@ -170,6 +170,19 @@ def test_decode_reduce_matches_numpy_rebuild(b):
     assert np.array_equal(out, acc)
     assert np.array_equal(oracle.decode_reduce(msgs, idx, w.E, w.G, oracle.ACC_FP32, bits=b),
                           f32_to_bf16_bits_lib(acc))
+    # the bf16 chain, exactly: every term and every partial sum through the library's conversion
+    chain = None
+    for mg in msgs:
+        codes, _ = unpack_bits(mg.codes, w.r, b)
+        s = group_expand(bits_to_f32(mg.scale), w.G, w.r)
+        z = group_expand(bits_to_f32(mg.zero), w.G, w.r)
+        xh = np.empty((w.T, w.E), np.float32)
+        xh[:, comp] = (codes.astype(np.float32) * s + z).astype(np.float32)
+        xh[:, idx] = bits_to_f32(mg.outl)
+        term = bits_to_f32(f32_to_bf16_bits_lib(xh))
+        chain = term if chain is None else bits_to_f32(f32_to_bf16_bits_lib((chain + term).astype(np.float32)))
+    got = oracle.decode_reduce(msgs, idx, w.E, w.G, oracle.ACC_BF16, bits=b)
+    assert np.array_equal(bits_to_f32(got), chain)
 
 
 @pytest.mark.parametrize("b", (3, 6))

@@ -200,8 +200,22 @@ def test_decode_reduce_matches_independent_dequant_sum():
     assert np.array_equal(out, acc)
     out16 = oracle.decode_reduce(msgs, idx, w.E, w.G, oracle.ACC_FP32, out_fp32=False)
     assert np.array_equal(out16, f32_to_bf16_bits_lib(acc))
-    # the bf16 chain stays within bf16 rounding of the fp32 result
-    outb = bits_to_f32(oracle.decode_reduce(msgs, idx, w.E, w.G, oracle.ACC_BF16))
+    # the bf16 chain, rebuilt exactly: every term and every partial sum through the library's
+    # bf16 conversion (the term is the fp32 value code * scale + zero rounded once)
+    chain = None
+    for mg in msgs:
+        codes, _ = unpack_codes(mg.codes, w.r)
+        s = group_expand(bits_to_f32(mg.scale), w.G, w.r)
+        z = group_expand(bits_to_f32(mg.zero), w.G, w.r)
+        xh = np.empty((w.T, w.E), np.float32)
+        xh[:, comp] = (codes.astype(np.float32) * s + z).astype(np.float32)
+        xh[:, idx] = bits_to_f32(mg.outl)
+        term = bits_to_f32(f32_to_bf16_bits_lib(xh))
+        chain = term if chain is None else bits_to_f32(f32_to_bf16_bits_lib((chain + term).astype(np.float32)))
+    outb_bits = oracle.decode_reduce(msgs, idx, w.E, w.G, oracle.ACC_BF16)
+    assert np.array_equal(bits_to_f32(outb_bits), chain)
+    # ... and it stays within bf16 rounding of the fp32 result
+    outb = bits_to_f32(outb_bits)
     scale = np.zeros_like(acc)
     for mg in msgs:
         scale += np.abs(bits_to_f32(oracle.decode_reduce([mg], idx, w.E, w.G, oracle.ACC_FP32)))
