@@ -61,6 +61,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-configs", action="store_true", help="skip the other configurations")
     ap.add_argument("--calibrate-chunks", type=int, default=8)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run an elementwise kernel that reads and writes 256 MiB: the known-size "
+                         "dispatch that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     return ap.parse_args()
 
 
@@ -315,6 +318,13 @@ def main():
     share_gbs = (B_enc / N + B_dec) / ((enc1_us + dec_ms * 1e3) * 1e-6) / 1e9
 
     ceiling = copy_ceiling(dev)
+    if args.copy_probe:
+        a = torch.zeros(1 << 26, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.bitwise_not(a, out=b)  # (the only bitwise_not of the run: found by name)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---- calibration throughput (offline path, reported separately) ----------------------
     wc = wl.CALIBRATION

@@ -150,6 +150,11 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     const u32x4 dp8 = drec[(seg * 64u + ln) * 2u];
     const u32x4 rec1 = drec[(seg * 64u + ln) * 2u + 1u];
     const uint2 sg = dseg[seg];
+    // (where segments are likely to have more than 64 slots, the second record leaves with the
+    // first instead of waiting for the segment's counts)
+    const bool eager2 = a.patch_slots > 64;
+    u32x4 rec2 = {0u, 0u, 0u, 0u};
+    if (eager2) rec2 = reinterpret_cast<const u32x4 *>(a.plan + a.off_drec2)[seg * 64u + ln];
     const PlanHeader *ph = reinterpret_cast<const PlanHeader *>(a.plan);
     if (ph->magic != kPlanMagic || ph->status != kPlanOk || ph->E != a.E || ph->k != a.k ||
         ph->G != a.G || ph->dir_P != P)
@@ -157,14 +162,18 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
 
     // slots and selected columns of this segment
     const uint32_t q_lo = sg.x & 0xFFFFu, n_q = sg.x >> 16;
+    // the wave's LDS area holds the segment's first `cap` slots; the slots past them (a
+    // segment far denser in selected features than the row's average) are gathered from
+    // memory, feature by feature
+    const uint32_t cap = static_cast<uint32_t>(a.patch_slots);
+    const uint32_t n_ql = min(n_q, cap);
     const uint32_t s_lo = sg.y & 0xFFFFu, n_sel = sg.y >> 16;
 
     // the segment's ln-th and (64 + ln)-th slot and selected feature (zero where there is
     // none); the second record is fetched only where a segment has that many
     const uint2 slot8 = make_uint2(rec1.x, rec1.y);
     const uint32_t sel0 = rec1.z;
-    u32x4 rec2 = {0u, 0u, 0u, 0u};
-    if (n_q > 64 || n_sel > 64)
+    if (!eager2 && (n_q > 64 || n_sel > 64))
         rec2 = reinterpret_cast<const u32x4 *>(a.plan + a.off_drec2)[seg * 64u + ln];
     uint32_t d[P];
     {
@@ -210,8 +219,8 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     }
     u32x4 win_b = {0u, 0u, 0u, 0u}, win_b2 = {0u, 0u, 0u, 0u};
     // (only where the next lane of the slot's pass does not load that window anyway)
-    const bool load_b = ln < n_q && (slot8.y & kDirLoadB8) != 0;
-    const bool load_b2 = 64u + ln < n_q && (rec2.y & kDirLoadB8) != 0;
+    const bool load_b = ln < n_ql && (slot8.y & kDirLoadB8) != 0;
+    const bool load_b2 = 64u + ln < n_ql && (rec2.y & kDirLoadB8) != 0;
     if (load_b) win_b = *reinterpret_cast<const u32x4_a4 *>(yrow + (slot8.y & 0x1FFFFu));
     if (load_b2) win_b2 = *reinterpret_cast<const u32x4_a4 *>(yrow + (rec2.y & 0x1FFFFu));
 
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
             const uint32_t nby = __builtin_amdgcn_update_dpp(0u, raw[p].y, 0x130, 0xF, 0xF, false);
             const uint32_t nbz = __builtin_amdgcn_update_dpp(0u, raw[p].z, 0x130, 0xF, 0xF, false);
             const uint32_t nbw = __builtin_amdgcn_update_dpp(0u, raw[p].w, 0x130, 0xF, 0xF, false);
-            if (has_slot) {
+            if (has_slot && my_slot[p] < cap) {
                 *reinterpret_cast<u32x4 *>(slots + 32u * my_slot[p]) = raw[p];
                 *reinterpret_cast<u32x4 *>(slots + 32u * my_slot[p] + 16u) = u32x4{nb, nby, nbz, nbw};
             }
@@ -266,9 +275,9 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     }
     if (load_b) *reinterpret_cast<u32x4 *>(slots + 32u * ln + 16u) = win_b;
     if (load_b2) *reinterpret_cast<u32x4 *>(slots + 32u * (64u + ln) + 16u) = win_b2;
-    for (uint32_t q0 = 128; q0 < n_q; q0 += 64) {  // more than 128 slots in a segment: rare
+    for (uint32_t q0 = 128; q0 < n_ql; q0 += 64) {  // more than 128 slots in a segment: rare
         const uint32_t q = q0 + ln;
-        if (q < n_q) {
+        if (q < n_ql) {
             const uint32_t y1 = dslot8[q_lo + q].y;
             if (y1 & kDirLoadB8)
                 *reinterpret_cast<u32x4 *>(slots + 32u * q + 16u) =
@@ -288,7 +297,7 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
         for (uint32_t p0 = 0; p0 < n_sel; p0 += 64) {
             const uint32_t p = p0 + ln, pc = min(p, n_sel - 1u);
             const uint32_t e = p0 == 0 ? sel0 : (p0 == 64 ? rec2.z : dsel[s_lo + pc]);
-            const bool far = (e & kDirFar) != 0;
+            const bool far = (e & kDirFar) != 0 || (e >> 5) - q_lo >= cap;  // in no slot, or in none that LDS holds
             uint32_t val = TPQ_LDS_HW(slots + (far ? 0u : e - 32u * q_lo));
             if (far) val = TPQ_HW(yrow + 2u * static_cast<uint32_t>(idx[s_lo + pc]));
             if constexpr (HOP) {  // received + own, in bf16
@@ -299,8 +308,8 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
             if (p < n_sel) outl[p] = static_cast<uint16_t>(val);
         }
     }
-    for (uint32_t q0 = 0; q0 < n_q; q0 += 64) {
-        const uint32_t q = q0 + ln, qc = min(q, n_q - 1u);
+    for (uint32_t q0 = 0; q0 < n_ql; q0 += 64) {
+        const uint32_t q = q0 + ln, qc = min(q, n_ql - 1u);
         const uint2 ent = q0 == 0 ? slot8 : (q0 == 64 ? make_uint2(rec2.x, rec2.y) : dslot8[q_lo + qc]);
         const uint8_t *sl = slots + 32u * qc;
         const uint32_t nib = ent.x;
@@ -321,14 +330,42 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
             g.w = TPQ_FAR(tab.w);
 #undef TPQ_FAR
         }
-        if (q < n_q) *reinterpret_cast<u32x4 *>(slots + 32u * q) = g;
+        if (q < n_ql) *reinterpret_cast<u32x4 *>(slots + 32u * q) = g;
     }
-#undef TPQ_HW
-#undef TPQ_LDS_HW
     wave_lds_fence();
 #pragma unroll
     for (int p = 0; p < P; ++p)
-        if (d[p] & kDir16Slot) v[p] = *reinterpret_cast<const u32x4 *>(slots + 32u * my_slot[p]);
+        if ((d[p] & kDir16Slot) && my_slot[p] < cap) v[p] = *reinterpret_cast<const u32x4 *>(slots + 32u * my_slot[p]);
+    if (n_q > cap) {
+        // the lanes whose slot LDS does not hold: a slot's entry gives each feature's column,
+        // or its byte offset in the two windows (the lane's own, and the one 8 columns on,
+        // pulled back to end with the row)
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if ((d[p] & kDir16Slot) && my_slot[p] >= cap) {
+                const u32x4 tab = dirr[q_lo + my_slot[p]];
+                const uint32_t wa = 2u * (d[p] & 0x3FFFu);
+                const uint32_t wb = min(wa + 8u, static_cast<uint32_t>(a.E) - 8u);
+                const uint32_t t4[4] = {tab.x, tab.y, tab.z, tab.w};
+                uint32_t g4[4];
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    uint32_t hw[2];
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        const uint32_t en = (t4[w2] >> (16 * h2)) & 0xFFFFu;
+                        const uint32_t col = (en & kDirWide) ? (en & 0x7FFFu)
+                                                             : (en < 16u ? wa + (en >> 1) : wb + ((en - 16u) >> 1));
+                        hw[h2] = TPQ_HW(yrow + 2u * col);
+                    }
+                    g4[w2] = hw[0] | (hw[1] << 16);
+                }
+                v[p] = u32x4{g4[0], g4[1], g4[2], g4[3]};
+            }
+        }
+    }
+#undef TPQ_HW
+#undef TPQ_LDS_HW
 
     if constexpr (HOP) {
         // features <- bf16(x_hat (+) feature): x_hat = code * scale + zero as in decode_reduce,
@@ -667,7 +704,12 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
         a.off_drec = o.drec;
         a.off_drec2 = o.drec2;
     }
-    a.patch_slots = a.dslots < 64 * P ? a.dslots : 64 * P;
+    // LDS slots per wave: room for a segment with 5/4 of the row's average share of the slots
+    // and 8 more (a denser segment gathers the rest from memory), never more than a segment
+    // or the row can have
+    a.patch_slots = (5 * a.dslots / a.segs) / 4 + 8;
+    if (a.patch_slots > a.dslots) a.patch_slots = a.dslots;
+    if (a.patch_slots > 64 * P) a.patch_slots = 64 * P;
     if (a.patch_slots < 8 * P) a.patch_slots = 8 * P;  // (the codes pass through the same area: 256 P bytes)
     const bool is_static = a.inv_c != nullptr;
     const bool is_gen = a.bits != 4;

@@ -150,6 +150,28 @@ def test_outlier_patterns(name, cols):
     _codec_case(w, Ys, idx)
 
 
+@pytest.mark.parametrize("E,G,cols", [
+    (5120, 128, [5 + 31 * i for i in range(80)]),                      # every slot of the row in its first segment
+    (8192, 64, [3 + 11 * i for i in range(341)]),                      # two dense segments, two without a slot
+    (8192, 128, [3 + 11 * i for i in range(300)] + list(range(3300, 3341))),  # ... with a chunk cut by a long run
+    (8192, 64, [4000 + 9 * i for i in range(341)]),                    # dense from the middle of the row on
+], ids=["llama_width_first_segment", "large_width_two_segments", "large_width_with_run", "large_width_from_middle"])
+def test_segments_denser_than_the_slot_area(E, G, cols):
+    """Selected features crowded into part of the row: a segment then has more cut chunks than
+    the encoder's LDS area holds slots for, and gathers the rest from memory."""
+    T, N = 5, 2
+    idx = np.array(sorted(set(cols)), np.int32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(E + len(cols))
+    Ys = []
+    for i in range(N):
+        x = torch.randn((T, E), generator=g, device="cuda")
+        x[:, torch.as_tensor(idx.astype(np.int64), device="cuda")] *= 40.0
+        Ys.append(x.to(torch.bfloat16))
+    w = dataclasses.replace(wl.TINY, N=N, T=T, E=E, k=idx.size, G=G)
+    _codec_case(w, Ys, idx)
+
+
 def test_denormal_and_huge_values():
     E, G, T = 512, 128, 4
     x = torch.zeros((T, E), device="cuda")
