@@ -53,6 +53,7 @@ def _load():
         lib.orc_max_threads.restype = i32
         lib.orc_calibrate_update.argtypes = [vp, i64, i64, i32, i32, f32, vp, vp]
         lib.orc_calibrate_finalize.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        lib.orc_linear.argtypes = [vp, i64, i64, i32, vp, i32, i64, vp, i64, vp, i32]
         lib.orc_encode.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         lib.orc_decode_reduce.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp,
                                           i32, i32, vp, i32]
@@ -150,6 +151,24 @@ def encode(Y, idx_sorted, G: int, threads: int = 1, bits: int = 4) -> Message:
     if rc:
         raise ValueError("orc_encode: bad arguments")
     return msg
+
+
+def linear(X, Wt, threads: int = 1, with_magnitude: bool = False):
+    """Sec. 2, f^(i)(x^(i)) = x^(i) W^(i): X bf16 [T,K], Wt bf16 [E,K] (W^(i) transposed) ->
+    bf16 bits [T,E], every output summed in float64 and rounded once.  with_magnitude: also
+    sum_k |x w| per output (float64), the scale of an accumulation-order error."""
+    X, Wt = _u16(X), _u16(Wt)
+    T, K = X.shape
+    E, K2 = Wt.shape
+    if K != K2:
+        raise ValueError("orc_linear: inner dimensions differ")
+    Y = np.empty((T, E), np.uint16)
+    mag = np.empty((T, E), np.float64) if with_magnitude else None
+    rc = _load().orc_linear(_ptr(X), T, K, K, _ptr(Wt), E, K, _ptr(Y), E,
+                            _ptr(mag) if with_magnitude else None, threads)
+    if rc:
+        raise ValueError("orc_linear: bad arguments")
+    return (Y, mag) if with_magnitude else Y
 
 
 def encode_bits(Y, idx_sorted, G: int, bits: int, threads: int = 1) -> Message:

@@ -61,6 +61,15 @@
  *   and then an optional bias (bf16 [E]), each as one more term of the same
  *   accumulation (fp32 add, or bf16-rounded add in the literal bf16 chain).
  *
+ *   the producer of the partial sums (paper Sec. 2: device i holds the slice
+ *   W^(i) of a row-parallel linear layer and computes f^(i)(x^(i)) = x^(i) W^(i),
+ *   the tensor that is then compressed): orc_linear evaluates every output as the
+ *   sum of its K products in binary64 (each product of two bf16 values is exact
+ *   there, the sum of a few thousand of them is exact to about 2^-41 of the sum of
+ *   their magnitudes) and rounds once to bf16, ties to even -- the definition, not
+ *   any particular accumulation order.  orc_encode of that tensor is the
+ *   reference for a GEMM that compresses in its epilogue.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (brute force over all 16 codes in float64, verbatim outliers, half-step
  * error bound, closed-form bit counts, Irwin-Hall variance of the summed
@@ -336,6 +345,54 @@ int orc_encode(const uint16_t *Y, int64_t T, int64_t ldY, int E, int k, int G,
                    scale ? scale + t * ng : NULL, zero ? zero + t * ng : NULL);
     }
     free(comp);
+    return ORC_OK;
+}
+
+/* ---- the linear layer that produces the partial sums --------------------- */
+
+/* nearest bf16 of a finite double, ties to even: through the two bf16 neighbours
+ * of the value, compared in binary64 (no intermediate rounding to binary32) */
+static uint16_t f64_to_bf16(double v)
+{
+    float f = (float)v;            /* within half a binary32 ulp: picks the neighbourhood */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t lo_bits = u & 0xFFFF0000u;          /* towards zero */
+    float lo, hi;
+    memcpy(&lo, &lo_bits, sizeof lo);
+    uint32_t hi_bits = lo_bits + 0x00010000u;    /* one bf16 step away from zero */
+    memcpy(&hi, &hi_bits, sizeof hi);
+    double dl = fabs(v - (double)lo), dh = fabs((double)hi - v);
+    if (dl < dh) return (uint16_t)(lo_bits >> 16);
+    if (dh < dl) return (uint16_t)(hi_bits >> 16);
+    return (uint16_t)(((lo_bits >> 16) & 1u) ? (hi_bits >> 16) : (lo_bits >> 16));
+}
+
+/*
+ * Y[t][e] = bf16( sum_k X[t][k] * Wt[e][k] ), X bf16 [T][ldX], Wt bf16 [E][ldW] (one
+ * row per output feature: W^(i) transposed), Y bf16 [T][ldY].  mag (optional, double
+ * [T][E]) receives sum_k |X[t][k] * Wt[e][k]|, the scale of any accumulation error.
+ */
+int orc_linear(const uint16_t *X, int64_t T, int64_t ldX, int K, const uint16_t *Wt, int E,
+               int64_t ldW, uint16_t *Y, int64_t ldY, double *mag, int threads)
+{
+    if (!X || !Wt || !Y || T < 0 || K < 1 || E < 1 || ldX < K || ldW < K || ldY < E)
+        return ORC_ERR_ARG;
+    set_threads(threads);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0, am = 0.0;
+            for (int kk = 0; kk < K; ++kk) {
+                double prod = (double)bf16_to_f32(X[t * ldX + kk]) *
+                              (double)bf16_to_f32(Wt[(int64_t)e * ldW + kk]);
+                acc += prod;
+                am += fabs(prod);
+            }
+            Y[t * ldY + e] = f64_to_bf16(acc);
+            if (mag) mag[t * (int64_t)E + e] = am;
+        }
+    }
     return ORC_OK;
 }
 
