@@ -229,6 +229,36 @@ int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int
             uint16_t *const *scale, uint16_t *const *zero, uint16_t *const *outl,
             void *stream);
 
+/* ---- the linear layer with the compression in its epilogue (Sec. 2: device i computes
+ * f^(i)(x^(i)) = x^(i) W^(i), the partial sum that C^(i) compresses; Sec. 3, "Selecting
+ * High Precision Features", names the selection before the exchange as the overhead) ----
+ *     message = tpq_encode( bf16( X * Wt^T ) )
+ * for ONE device, without the partial sums going to memory: the product is accumulated
+ * in fp32 on the matrix cores, rounded to bf16 once, and compressed from registers.  The
+ * sums of the K products are taken in the matrix cores' own order, so the bf16 product can
+ * differ from a product summed otherwise in its last bit where the exact sum lies next to
+ * a rounding boundary; given that bf16 product, the message is exactly tpq_encode's.
+ *
+ * The weights are reordered once, offline (they and the selected features are static):
+ *   tpq_gemm_weights: Wt [device] bf16 [E][ldW], one row per output feature (W^(i)
+ *         transposed: the layout of a linear layer's weight), K columns used;
+ *         Wp [device] bf16 [E][K]: the rows of Wt in message order -- the r features that are
+ *         quantised, ascending, then the k selected ones, ascending.  plan as for tpq_encode.
+ *   tpq_gemm_encode: X [device] bf16 [T][ldX] (K columns used), Wp from tpq_gemm_weights;
+ *         codes, scale, zero, outl [device]: the device's message sections (layout L; outl is
+ *         ignored when k = 0, the other three when k = E);
+ *         Y_msg [device] bf16 [T][ldYm] or NULL: if given, also receives the rounded product
+ *         in message order (feature n < r = compacted feature n, n >= r = selected feature
+ *         n - r): what a device keeps when it takes its own partial sum unquantised.
+ *   K, ldW, ldX, ldYm: elements, multiples of 8; ldW, ldX >= K; ldYm >= E.  No plan is needed
+ *   by tpq_gemm_encode: the order is in Wp.  4-bit layouts only (TPQ_ERR_UNSUPPORTED
+ *   otherwise); T <= 65535 * 128. */
+int tpq_gemm_weights(const tpq_layout *L, const void *plan, const uint16_t *Wt, int64_t ldW,
+                     int K, uint16_t *Wp, void *stream);
+int tpq_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_t ldX, int K,
+                    const uint16_t *Wp, uint8_t *codes, uint16_t *scale, uint16_t *zero,
+                    uint16_t *outl, uint16_t *Y_msg, int64_t ldYm, void *stream);
+
 /* ---- decode + reduce (Sec. 2 D^(i) and the sum; Fig. 2 caption) ------------
  * out[t][j] = sum over the n_ranks messages of x_hat (selected features: the
  * bf16 value itself), in ascending device order, in original feature order.

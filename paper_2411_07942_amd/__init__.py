@@ -33,7 +33,7 @@ EXPORTS = [
     "tpq_plan_bytes", "tpq_plan_build", "tpq_plan_check",
     "tpq_calibrate_workspace_bytes", "tpq_calibrate", "tpq_calibrate_fixed",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
-    "tpq_encode", "tpq_hop", "tpq_decode_reduce", "tpq_decode_reduce_fused",
+    "tpq_encode", "tpq_hop", "tpq_gemm_weights", "tpq_gemm_encode", "tpq_decode_reduce", "tpq_decode_reduce_fused",
     "tpq_static_table_floats", "tpq_static_params", "tpq_encode_static", "tpq_decode_reduce_static",
 ]
 
@@ -92,6 +92,8 @@ def _load():
     lib.tpq_encode.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, vp]
     lib.tpq_time_next_launch.argtypes = [vp, vp]
     lib.tpq_hop.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, c_int, vp, vp, vp, vp, vp]
+    lib.tpq_gemm_weights.argtypes = [LP, vp, vp, i64, c_int, vp, vp]
+    lib.tpq_gemm_encode.argtypes = [LP, vp, i64, i64, c_int, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.tpq_decode_reduce.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, c_int, c_int, vp, i64, vp]
     lib.tpq_decode_reduce_fused.argtypes = [LP, vp, c_int, i64, vp, vp, vp, vp, vp, i64, vp, c_int, c_int,
                                             vp, i64, vp]
@@ -311,6 +313,47 @@ def hop(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], in_msgs: Seque
         out_msgs: Sequence[Message], accum: int = ACC_BF16, stream=None) -> None:
     """Ring step: out_msgs[i] = encode(bf16(dequantised in_msgs[i] (+) Y[i])), one launch."""
     hop_call(L, plan, Y, in_msgs, out_msgs, accum)(stream)
+
+
+def gemm_weights(L: Layout, plan: torch.Tensor, Wt: torch.Tensor, stream=None) -> torch.Tensor:
+    """Rows of Wt (bf16 [E, K], one row per output feature) in message order: the weights
+    tpq_gemm_encode takes."""
+    lib = _load()
+    assert Wt.dtype == torch.bfloat16 and Wt.dim() == 2 and Wt.shape[0] == L.E and Wt.stride(1) == 1
+    K = Wt.shape[1]
+    Wp = torch.empty((L.E, K), dtype=torch.bfloat16, device=Wt.device)
+    _check(lib.tpq_gemm_weights(ctypes.byref(L), _ptr(plan), _ptr(Wt), Wt.stride(0), K, _ptr(Wp),
+                                _stream(stream)), "tpq_gemm_weights")
+    return Wp
+
+
+def gemm_encode_call(L: Layout, X: torch.Tensor, Wp: torch.Tensor, msg: Message,
+                     Y_msg: Optional[torch.Tensor] = None):
+    """Marshal a tpq_gemm_encode call once; the returned function(stream=None) issues it.
+    X bf16 [T, K]; Wp from gemm_weights; Y_msg: optional bf16 [T, >= E] for the rounded product
+    in message order."""
+    lib = _load()
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    assert Wp.dtype == torch.bfloat16 and Wp.is_contiguous() and Wp.shape == (L.E, X.shape[1])
+    T, K = X.shape
+    ldX = X.stride(0) if T > 1 else max(K, X.stride(0))
+    ldYm = 0
+    if Y_msg is not None:
+        assert Y_msg.dtype == torch.bfloat16 and Y_msg.shape[0] == T and Y_msg.stride(1) == 1
+        ldYm = Y_msg.stride(0) if T > 1 else max(L.E, Y_msg.stride(0))
+    args = (ctypes.byref(L), _ptr(X), T, ldX, K, _ptr(Wp), _ptr(msg.codes), _ptr(msg.scale), _ptr(msg.zero),
+            _ptr(msg.outl), _ptr(Y_msg) if Y_msg is not None else None, ldYm)
+    keep = (L, X, Wp, msg, Y_msg)
+
+    def call(stream=None, _keep=keep):
+        _check(lib.tpq_gemm_encode(*args, _stream(stream)), "tpq_gemm_encode")
+    return call
+
+
+def gemm_encode(L: Layout, X: torch.Tensor, Wp: torch.Tensor, msg: Message,
+                Y_msg: Optional[torch.Tensor] = None, stream=None) -> None:
+    """msg = encode(bf16(X @ W)) for one device, the product never stored (unless Y_msg asks)."""
+    gemm_encode_call(L, X, Wp, msg, Y_msg)(stream)
 
 
 def decode_reduce_call(L: Layout, plan: torch.Tensor, msgs: Sequence[Message], out: torch.Tensor,

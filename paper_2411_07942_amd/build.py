@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libtpq.so")
 
-SOURCES = ["tpq_api.cpp", "tpq_plan.hip", "tpq_calibrate.hip", "tpq_encode.hip", "tpq_decode.hip"]
+SOURCES = ["tpq_api.cpp", "tpq_plan.hip", "tpq_calibrate.hip", "tpq_encode.hip", "tpq_decode.hip", "tpq_gemm.hip"]
 
 # -ffp-contract=off: codes, scales and sums must match a non-fused IEEE evaluation.
 # -fno-honor-nans: inputs are finite by contract; without it every min / max drags a

@@ -273,6 +273,39 @@ int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y, 
     return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream));
 }
 
+int tpq_gemm_weights(const tpq_layout *L, const void *plan, const uint16_t *Wt, int64_t ldW, int K,
+                     uint16_t *Wp, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;
+    if (K < 8 || ldW < K) return TPQ_ERR_SHAPE;
+    if ((K % 8) != 0 || (ldW % 8) != 0) return TPQ_ERR_ALIGN;
+    if (!plan || !Wt || !Wp) return TPQ_ERR_NULL;
+    if (!aligned16(plan) || !aligned16(Wt) || !aligned16(Wp)) return TPQ_ERR_ALIGN;
+    return launch_gemm_weights(L, plan, Wt, ldW, K, Wp, static_cast<hipStream_t>(stream));
+}
+
+int tpq_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_t ldX, int K,
+                    const uint16_t *Wp, uint8_t *codes, uint16_t *scale, uint16_t *zero,
+                    uint16_t *outl, uint16_t *Y_msg, int64_t ldYm, void *stream)
+{
+    int rc = check_layout(L);
+    if (rc) return rc;
+    if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;
+    if (T < 0 || K < 8 || ldX < K || (Y_msg && ldYm < L->E)) return TPQ_ERR_SHAPE;
+    if ((K % 8) != 0 || (ldX % 8) != 0 || (Y_msg && (ldYm % 8) != 0)) return TPQ_ERR_ALIGN;
+    if (!X || !Wp) return TPQ_ERR_NULL;
+    if (L->r > 0 && (!codes || !scale || !zero)) return TPQ_ERR_NULL;
+    if (L->k > 0 && !outl) return TPQ_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wp) || !aligned16(codes) || !aligned16(scale) || !aligned16(zero) ||
+        !aligned16(outl) || !aligned16(Y_msg))
+        return TPQ_ERR_ALIGN;
+    if (T == 0) return TPQ_OK;
+    return launch_gemm_encode(L, X, T, ldX, K, Wp, codes, scale, zero, outl, Y_msg, ldYm,
+                              static_cast<hipStream_t>(stream));
+}
+
 int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int64_t ldY,
             int n_ranks, int64_t T, const uint8_t *const *in_codes, const uint16_t *const *in_scale,
             const uint16_t *const *in_zero, const uint16_t *const *in_outl, int accum,

@@ -294,6 +294,11 @@ int launch_encode(const EncodeArgs &a, const RankPtrs &Y, const RankPtrs &codes,
 int launch_decode(const DecodeArgs &a, const RankPtrs &codes, const RankPtrs &scale,
                   const RankPtrs &zero, const RankPtrs &outl, int accum, int out_dtype,
                   hipStream_t s);
+int launch_gemm_weights(const tpq_layout *L, const void *plan, const uint16_t *Wt, int64_t ldW, int K,
+                        uint16_t *Wp, hipStream_t s);
+int launch_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_t ldX, int K,
+                       const uint16_t *Wp, uint8_t *codes, uint16_t *scale, uint16_t *zero,
+                       uint16_t *outl, uint16_t *Ymsg, int64_t ldYm, hipStream_t s);
 // calibration workspace: up to kCalMaxParts slices of partial minima / maxima
 constexpr int kCalMaxParts = 128;
 size_t calibrate_workspace_bytes(int E);

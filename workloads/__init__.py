@@ -200,3 +200,22 @@ def calibration_sequence(w: Workload, block: int, rank: int, seq: int, device="c
 
 def n_cal_sequences(w: Workload) -> int:
     return w.cal_tokens // w.cal_seq if w.cal_seq else 0
+
+
+def linear_inputs(T: int, K: int, E: int, outlier_rows, seed: int, device="cpu", integer: bool = False):
+    """Inputs of one device's row-parallel linear layer (Sec. 2): activations X bf16 [T,K] and
+    the weight slice Wt bf16 [E,K], one row per output feature.  The rows in `outlier_rows` are
+    scaled up so that those output features get the enormous range of the paper's Fig. 1.
+    integer: small integers instead (every product and every partial sum is then exact in
+    fp32, whatever the order of the additions)."""
+    g = _gen(device, 7_000_003 * int(seed) + 13 * T + 17 * K + 19 * E)
+    if integer:
+        X = torch.randint(-3, 4, (T, K), generator=g, device=device).to(torch.float32)
+        Wt = torch.randint(-3, 4, (E, K), generator=g, device=device).to(torch.float32)
+    else:
+        X = torch.randn((T, K), generator=g, device=device)
+        Wt = torch.randn((E, K), generator=g, device=device) / math.sqrt(K)
+        rows = torch.as_tensor(np.asarray(outlier_rows, np.int64), device=device)
+        if rows.numel():
+            Wt[rows] *= 30.0
+    return X.to(torch.bfloat16), Wt.to(torch.bfloat16)
