@@ -16,6 +16,8 @@ This script adds what a deployment asks next, one JSON line per section:
   bits    the Llama-2-13B-shaped block at the other code widths (2, 3, 5, 6, 8 bits beside 4);
   fused   the Llama-2-13B-shaped block: decode_reduce with the residual and bias added inside the
           kernel, beside decode_reduce followed by two elementwise additions;
+  gemm    one device's linear layer at the Llama-2-13B shape with the compression in the GEMM's
+          epilogue, beside the library GEMM followed by tpq_encode;
   static  the Llama-2-13B-shaped block in the static symmetric mode (per device and feature steps
           from calibration; only codes and selected features travel): encode of all ranks, of one
           rank, decode_reduce in both accumulate modes.
@@ -311,16 +313,62 @@ def section_static(tpq, wl, args):
             "note": "algorithmic bytes exclude the step tables (160 KB per device, shared by all rows, served by L2)"}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def section_gemm(tpq, wl, args):
+    """One device's row-parallel linear layer at the Llama-2-13B shape with the compression in
+    the GEMM's epilogue (tpq_gemm_encode), beside the library GEMM (torch.matmul) followed by
+    tpq_encode with the bf16 partial sums in memory between them.  K = 13824 / 8 (MLP down
+    projection) and 5120 / 8 (attention output projection)."""
+    w = wl.LLAMA_PREFILL
+    T, E = w.T, w.E
+    dev = "cuda"
+    L = tpq.layout_init(E, w.k, w.G)
+    idx = idx_for(wl, w)
+    plan = tpq.plan_build(L, torch.from_numpy(idx).to(dev))
+    tpq.plan_check(L, plan)
+    shapes = []
+    for K in (1728, 640):
+        sets = []
+        for s in range(4):
+            X, Wt = wl.linear_inputs(T, K, E, idx, 100 + s, device=dev)
+            Wp = tpq.gemm_weights(L, plan, Wt)
+            msg = tpq.Message(L, T, dev)
+            Y = torch.empty((T, E), dtype=torch.bfloat16, device=dev)
+            Wk = Wt.t()                                   # [K, E] view: torch.matmul(X, Wk) = X Wt^T
+            enc1 = tpq.encode_call(L, plan, [Y], [msg])
+
+            def lib_gemm(X=X, Wk=Wk, Y=Y):
+                torch.matmul(X, Wk, out=Y)
+
+            def unfused(lib_gemm=lib_gemm, enc1=enc1):
+                lib_gemm()
+                enc1()
+            sets.append(dict(fused=tpq.gemm_encode_call(L, X, Wp, msg), fused_y=tpq.gemm_encode_call(L, X, Wp, msg, Y),
+                             lib_gemm=lib_gemm, unfused=unfused, enc1=enc1, keep=(X, Wt, Wp, msg, Y)))
+        t = {k: round(timed([s[k] for s in sets], 40) / len(sets), 2) for k in ("fused", "fused_y", "lib_gemm", "unfused", "enc1")}
+        flop = 2.0 * T * K * E
+        shapes.append({"K": K, "us": t, "fused_TFLOPs": round(flop / t["fused"] / 1e6, 1),
+                       "fused_frac_of_mfma_peak": round(flop / t["fused"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "lib_gemm_TFLOPs": round(flop / t["lib_gemm"] / 1e6, 1)})
+    return {"section": "llama2_13b_prefill_gemm_epilogue", "T": T, "E": E, "shapes": shapes,
+            "note": "fused = tpq_gemm_encode (message only); fused_y = the same, also storing the bf16 product; "
+                    "lib_gemm = torch.matmul into a bf16 tensor; unfused = lib_gemm then tpq_encode of that tensor; "
+                    "enc1 = that tpq_encode alone"}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused,hop")
+    ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused,hop,gemm")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")
     import paper_2411_07942_amd as tpq
     import workloads as wl
     table = {"llama": section_llama, "gemma": section_gemma, "large": section_large,
-             "static": section_static, "bits": section_bits, "fused": section_fused, "hop": section_hop}
+             "static": section_static, "bits": section_bits, "fused": section_fused, "hop": section_hop,
+             "gemm": section_gemm}
     for name in args.sections.split(","):
         print(json.dumps(table[name](tpq, wl, args)), flush=True)
 

@@ -252,7 +252,7 @@ int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int
  *         n - r): what a device keeps when it takes its own partial sum unquantised.
  *   K, ldW, ldX, ldYm: elements, multiples of 8; ldW, ldX >= K; ldYm >= E.  No plan is needed
  *   by tpq_gemm_encode: the order is in Wp.  4-bit layouts only (TPQ_ERR_UNSUPPORTED
- *   otherwise); T <= 65535 * 128. */
+ *   otherwise); T <= 65535 * 64. */
 int tpq_gemm_weights(const tpq_layout *L, const void *plan, const uint16_t *Wt, int64_t ldW,
                      int K, uint16_t *Wp, void *stream);
 int tpq_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_t ldX, int K,

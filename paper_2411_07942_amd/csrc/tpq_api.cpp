@@ -294,6 +294,8 @@ int tpq_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_t l
     if (rc) return rc;
     if (L->bits != 4) return TPQ_ERR_UNSUPPORTED;
     if (T < 0 || K < 8 || ldX < K || (Y_msg && ldYm < L->E)) return TPQ_ERR_SHAPE;
+    // (the kernel addresses both operands through buffer descriptors with 31-bit sizes)
+    if (static_cast<int64_t>(L->E) * K * 2 >= (1ll << 31) || T * ldX * 2 >= (1ll << 31)) return TPQ_ERR_SHAPE;
     if ((K % 8) != 0 || (ldX % 8) != 0 || (Y_msg && (ldYm % 8) != 0)) return TPQ_ERR_ALIGN;
     if (!X || !Wp) return TPQ_ERR_NULL;
     if (L->r > 0 && (!codes || !scale || !zero)) return TPQ_ERR_NULL;

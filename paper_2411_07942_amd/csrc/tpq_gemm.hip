@@ -23,12 +23,13 @@ namespace tpq {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmTF = 256;   // features per workgroup tile (2 waves of 128)
-constexpr int kGemmTT = 128;   // tokens per workgroup tile (2 waves of 64)
-constexpr int kGemmBK = 32;    // k per stage
-constexpr int kGemmRow = 80;   // LDS bytes per operand row of a stage: 64 of data, 16 of padding
-                               // (16 consecutive rows then start in 16 different 16-byte bank groups)
-constexpr int kGemmStage = (kGemmTF + kGemmTT) * kGemmRow;
+// k per stage: a row of a stage is 128 bytes, one whole cache line per request to L2
+constexpr int kGemmBK = 64;
+constexpr int kGemmPPR = kGemmBK / 8;        // 16-byte pieces per operand row of a stage
+constexpr int kGemmRow = kGemmBK * 2;        // LDS bytes per operand row of a stage
+// piece p of row m sits at slot p ^ (m % 8): the lanes that fetch the same piece of consecutive
+// rows (an MFMA operand) spread over all banks, and so do the lanes that write a row's pieces
+__device__ __forceinline__ uint32_t gemm_swz(uint32_t row) { return row & 7u; }
 
 // Rows of Wt ([E][ldW], one row per output feature) -> Wp [E][K] in message order.
 __global__ __launch_bounds__(256) void k_gemm_weights(const uint8_t *plan, int E, int k, int G, int r,
@@ -56,12 +57,15 @@ struct GemmArgs {
 };
 
 // One (token block of 32) of a wave's accumulators -> message.  y[fb][v]: feature
-// F0 + 32 fb + 8 (v / 4) + 4 h + v % 4 of token t, h = lane / 32.  RAGGED: the wave's 128
-// features are not all quantised ones (the row's last groups, the outlier section, the
-// padding past E); otherwise nothing needs a mask.
-template <int G, bool RAGGED>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][16], uint32_t F0, int64_t t,
-                                              bool t_ok, uint32_t h, float *xch, uint32_t wm, uint32_t tslot)
+// F0 + 32 fb + 8 (v / 4) + 4 h + v % 4 of token t, h = lane / 32 (a wave has 64 features:
+// fb = 0, 1).  RAGGED: the wave's 64 features are not all quantised ones (the row's last
+// groups, the outlier section, the padding past E); otherwise nothing needs a mask.
+// A group wider than the wave's 64 features lies in G / 64 waves of the workgroup that
+// work on the same tokens: their minima and maxima meet in LDS (xch).
+template <int G, int WF, bool RAGGED>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[2][16], uint32_t F0, int64_t t,
+                                              bool t_ok, uint32_t h, float *xch, uint32_t wm, uint32_t tslot,
+                                              uint32_t n_tslots)
 {
     constexpr float kBig = 3.3895314e38f;  // the largest finite bf16
     const int r = a.r;
@@ -69,7 +73,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][1
     if (a.Ymsg && t_ok) {
         uint16_t *yrow = a.Ymsg + t * a.ldYm;
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb) {
+        for (int fb = 0; fb < 2; ++fb) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t f = F0 + 32u * fb + 8u * j + 4u * h;
@@ -83,9 +87,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][1
         }
     }
     // min / max per block of 32 features, over the quantised ones
-    float mn[4], mx[4];
+    float mn[2], mx[2];
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb) {
+    for (int fb = 0; fb < 2; ++fb) {
         float lo = kBig, hi = -kBig;
         const int lim = r - static_cast<int>(F0 + 32u * fb + 4u * h);  // element offsets below this are quantised
 #pragma unroll
@@ -100,57 +104,55 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][1
     if (G >= 64) {
         mn[0] = mn[1] = fminf(mn[0], mn[1]);
         mx[0] = mx[1] = fmaxf(mx[0], mx[1]);
-        mn[2] = mn[3] = fminf(mn[2], mn[3]);
-        mx[2] = mx[3] = fmaxf(mx[2], mx[3]);
     }
-    if (G >= 128) {
-        mn[0] = mn[1] = mn[2] = mn[3] = fminf(mn[0], mn[2]);
-        mx[0] = mx[1] = mx[2] = mx[3] = fmaxf(mx[0], mx[2]);
-    }
-    if (G == 256) {
-        // the group's other half is the neighbouring wave's (same tokens): through LDS
-        float *mine = xch + ((wm * 2u + 0u) * 128u + tslot) * 2u;
-        const float *other = xch + (((wm ^ 1u) * 2u + 0u) * 128u + tslot) * 2u;
+    constexpr int WPG = G > 64 ? G / 64 : 1;  // waves per group
+    static_assert(WPG <= WF, "a group must lie inside the workgroup's features");
+    if (WPG > 1) {
+        float *mine = xch + (wm * n_tslots + tslot) * 2u;
         if (h == 0) {
             mine[0] = mn[0];
             mine[1] = mx[0];
         }
         __syncthreads();
-        const float omn = other[0], omx = other[1];
+        const uint32_t w0 = wm & ~static_cast<uint32_t>(WPG - 1);
+        float lo = kBig, hi = -kBig;
+#pragma unroll
+        for (int q = 0; q < WPG; ++q) {
+            const float *o = xch + ((w0 + q) * n_tslots + tslot) * 2u;
+            lo = fminf(lo, o[0]);
+            hi = fmaxf(hi, o[1]);
+        }
         __syncthreads();
-        mn[0] = mn[1] = mn[2] = mn[3] = fminf(mn[0], omn);
-        mx[0] = mx[1] = mx[2] = mx[3] = fmaxf(mx[0], omx);
+        mn[0] = mn[1] = lo;
+        mx[0] = mx[1] = hi;
     }
     // zero, bf16 scale, reciprocal (the arithmetic of the stand-alone encoder); lane h = 0
     // stores the scales, its partner the zeros
-    float inv[4];
-    constexpr int NG = G >= 128 ? 1 : 128 / G;        // groups in the wave's 128 features
-    constexpr int FB_PER_G = G >= 128 ? 4 : G / 32;   // blocks per group
+    float inv[2];
+    constexpr int NG = G == 32 ? 2 : 1;  // groups in the wave's 64 features
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-        const int fb = gi * FB_PER_G;
-        mn[fb] = mn[fb] + 0.0f;  // a zero minimum is stored as +0
-        const float s32 = div_by_15(mx[fb] - mn[fb]);
+        mn[gi] = mn[gi] + 0.0f;  // a zero minimum is stored as +0
+        const float s32 = div_by_15(mx[gi] - mn[gi]);
         const uint32_t sb = pack_bf16x2(s32, s32) & 0xFFFFu;
         const float s = bf16_bits_to_f32(sb);
         const bool constant = s < 1e-30f;
-        const float iv = constant ? 0.0f : reciprocal_of_scale(s);
-#pragma unroll
-        for (int q = 0; q < FB_PER_G; ++q) {
-            inv[fb + q] = iv;
-            mn[fb + q] = mn[fb];
-        }
-        const uint32_t g = G == 256 ? F0 / 256u : F0 / static_cast<uint32_t>(G) + gi;
-        const bool owner = G == 256 ? wm == 0 : true;
+        inv[gi] = constant ? 0.0f : reciprocal_of_scale(s);
+        const uint32_t g = G == 32 ? F0 / 32u + gi : F0 / static_cast<uint32_t>(G);
+        const bool owner = WPG == 1 || (wm & (WPG - 1)) == 0;
         if (t_ok && owner && g < static_cast<uint32_t>(a.ng)) {
             uint16_t *dst = reinterpret_cast<uint16_t *>((h ? a.zero : a.scale) + t * a.pitch_meta) + g;
-            *dst = static_cast<uint16_t>(h ? __float_as_uint(mn[fb]) >> 16 : (constant ? 0u : sb));
+            *dst = static_cast<uint16_t>(h ? __float_as_uint(mn[gi]) >> 16 : (constant ? 0u : sb));
         }
+    }
+    if (NG == 1) {
+        mn[1] = mn[0];
+        inv[1] = inv[0];
     }
     // codes: a lane has 4 consecutive features of every chunk (its low or its high half)
     uint8_t *crow = a.codes + t * a.pitch_codes;
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb) {
+    for (int fb = 0; fb < 2; ++fb) {
         uint32_t half[4];
         const int lim = r - static_cast<int>(F0 + 32u * fb + 4u * h);
 #pragma unroll
@@ -182,7 +184,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][1
     if (RAGGED && t_ok) {
         uint16_t *orow = reinterpret_cast<uint16_t *>(a.outl + t * a.pitch_outl);
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb) {
+        for (int fb = 0; fb < 2; ++fb) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int f = static_cast<int>(F0 + 32u * fb + 4u * h) + 8 * (v >> 2) + (v & 3);
@@ -192,124 +194,149 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, float (&y)[4][1
     }
 }
 
-template <int G>
-__global__ __launch_bounds__(256, 2) void k_gemm_encode(GemmArgs a)
+// Workgroup = WF x WT waves, each with a tile of 64 features x 64 tokens (four 32x32 blocks);
+// the workgroup's tile is 64 WF features x 64 WT tokens.  One LDS stage of 64 k; the next
+// stage's operands are loaded into registers while the current one is multiplied.
+template <int G, int WF, int WT>
+__global__ __launch_bounds__(64 * WF * WT, 768 / (64 * WF * WT)) void k_gemm_encode(GemmArgs a)
 {
+    constexpr int NT = 64 * WF * WT;            // threads
+    constexpr int ROWS_A = 64 * WF, ROWS_B = 64 * WT;
+    constexpr int NP = (ROWS_A + ROWS_B) * kGemmPPR / NT;  // 16-byte pieces per thread and stage
+    static_assert((ROWS_A + ROWS_B) * kGemmPPR % NT == 0 && (ROWS_A * kGemmPPR) % NT == 0, "pieces divide evenly");
+    constexpr int NPA = ROWS_A * kGemmPPR / NT;     // ... of which the weights'
+    constexpr int RPP = NT / kGemmPPR;              // rows the threads cover in one pass
     extern __shared__ u32x4 smem_gemm[];
     uint8_t *lds = reinterpret_cast<uint8_t *>(smem_gemm);
     const uint32_t tid = threadIdx.x, ln = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t wm = wave >> 1, wn = wave & 1u;
-    const uint32_t tileF = blockIdx.x * kGemmTF;
-    const int64_t tileT = static_cast<int64_t>(blockIdx.y) * kGemmTT;
+    const uint32_t wm = wave / WT, wn = wave % WT;
+    const uint32_t tileF = blockIdx.x * ROWS_A;
+    const int64_t tileT = static_cast<int64_t>(blockIdx.y) * ROWS_B;
     const int K = a.K;
 
-    // this thread's pieces of a stage: 4 of the weights' tile, 2 of the tokens'
-    // (piece = 16 bytes = 8 k; row = tid / 4 + 64 i, piece tid % 4)
-    const uint32_t prow = tid >> 2, pk = (tid & 3u) * 8u;
-    const uint16_t *ga[4], *gb[2];
+    // this thread's pieces of a stage (piece = 16 bytes = 8 k): row tid / 8 + RPP i of the
+    // weights' rows followed by the tokens' rows, piece tid % 8.  A piece's address is a
+    // uniform base (operand + the stage's first k) plus a 32-bit offset that never changes, so
+    // that no register is written on the way to a load but the load's own destination.
+    const uint32_t prow = tid / kGemmPPR, ppc = tid % kGemmPPR;
+    const int pk = static_cast<int>(ppc) * 8;
+    const int pkc = min(pk, K - 8);  // (K < 64: the pieces past K read a valid one, and count as zeros)
+    uint32_t voff[NP];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t f = min(tileF + prow + 64u * i, static_cast<uint32_t>(a.E) - 1u);
-        ga[i] = a.Wp + static_cast<int64_t>(f) * K;
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int64_t t = min(tileT + prow + 64 * i, a.T - 1);
-        gb[i] = a.X + t * a.ldX;
-    }
-    const uint32_t lds_piece = prow * kGemmRow + (tid & 3u) * 16u;
-
-    u32x4 ra[4], rb[2];
-    auto load_stage = [&](int k0) {
-        const int kk = k0 + static_cast<int>(pk);
-        const bool ok = kk < K;           // (K is a multiple of 8: a piece is inside or outside)
-        const int ks = ok ? kk : 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + ks);
-            if (!ok) ra[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < NP; ++i) {
+        if (i < NPA) {
+            const uint32_t f = min(tileF + prow + RPP * i, static_cast<uint32_t>(a.E) - 1u);
+            voff[i] = (f * static_cast<uint32_t>(K) + static_cast<uint32_t>(pkc)) * 2u;
+        } else {
+            const int64_t t = min(tileT + prow + RPP * (i - NPA), a.T - 1);
+            voff[i] = static_cast<uint32_t>((t * a.ldX + pkc) * 2);
         }
+    }
+    const uint32_t lds_piece = prow * kGemmRow + (ppc ^ gemm_swz(prow)) * 16u;
+
+    // The next stage is on its way in registers while one is multiplied.  Every load is
+    // unconditional: stage kt reads the 64 k from kb = min(64 kt, K - 64) on (the last, partial
+    // stage reads the last 64 k of the row, the stage past the end reads them again), and what
+    // a piece holds counts only if its k is inside the stage: zeros otherwise, put in when the
+    // piece goes to LDS -- nothing may touch a loaded register before its stage is due, or the
+    // wave waits for the load there.
+    const int k_last = max(K - kGemmBK, 0);
+    u32x4 rg[NP];
+    // (buffer loads: descriptor and the stage's k offset in scalar registers, the piece's
+    // offset in a vector register that never changes -- no address arithmetic in vector
+    // registers, which the register allocator would place in the loads' destinations)
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.Wp), 0, static_cast<int>(static_cast<int64_t>(a.E) * K * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.X), 0, static_cast<int>(((a.T - 1) * a.ldX + K) * 2), 0x00020000);
+    auto load_stage = [&](int kt) {
+        const int kb = min(kt * kGemmBK, k_last);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            rb[i] = *reinterpret_cast<const u32x4 *>(gb[i] + ks);
-            if (!ok) rb[i] = u32x4{0u, 0u, 0u, 0u};
-        }
+        for (int i = 0; i < NP; ++i)
+            rg[i] = __builtin_amdgcn_raw_buffer_load_b128(i < NPA ? ra : rb, voff[i], 2 * kb, 0);
     };
-    auto store_stage = [&](int s) {
-        uint8_t *base = lds + s * kGemmStage;
+    auto store_stage = [&](int kt) {
+        const int kpos = min(kt * kGemmBK, k_last) + pk;
+        const bool ok = kpos >= kt * kGemmBK && kpos < K;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4 *>(base + lds_piece + 64u * i * kGemmRow) = ra[i];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<u32x4 *>(base + kGemmTF * kGemmRow + lds_piece + 64u * i * kGemmRow) = rb[i];
+        for (int i = 0; i < NP; ++i)
+            *reinterpret_cast<u32x4 *>(lds + lds_piece + RPP * i * kGemmRow) = ok ? rg[i] : u32x4{0u, 0u, 0u, 0u};
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[2][2];
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb)
+    for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fb][tb][v] = 0.0f;
 
     // operand fetch: lane = (row of the 32x32 block, half of the 16 k)
-    const uint32_t frag = (ln & 31u) * kGemmRow + (ln >> 5) * 16u;
-    const uint32_t fa = (128u * wm) * kGemmRow + frag;
-    const uint32_t fbt = kGemmTF * kGemmRow + (64u * wn) * kGemmRow + frag;
+    const uint32_t frag = (ln & 31u) * kGemmRow;
+    const uint32_t fa = (64u * wm) * kGemmRow + frag;
+    const uint32_t fbt = (ROWS_A + 64u * wn) * kGemmRow + frag;
+    uint32_t fk[kGemmBK / 16];  // byte offset in the row of this lane's piece of k-step ks
+#pragma unroll
+    for (int ks = 0; ks < kGemmBK / 16; ++ks) fk[ks] = ((2u * ks + (ln >> 5)) ^ gemm_swz(ln & 31u)) * 16u;
 
     const int nkt = (K + kGemmBK - 1) / kGemmBK;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-    for (int kt = 0; kt < nkt; ++kt) {
-        const bool more = kt + 1 < nkt;
-        if (more) load_stage((kt + 1) * kGemmBK);
-        const uint8_t *st = lds + (kt & 1) * kGemmStage;
+    auto compute_stage = [&](const uint8_t *st) {
 #pragma unroll
         for (int ks = 0; ks < kGemmBK / 16; ++ks) {
-            u32x4 av[4], bv[2];
+            u32x4 av[2], bv[2];
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
-                av[fb] = *reinterpret_cast<const u32x4 *>(st + fa + 32u * fb * kGemmRow + 32u * ks);
+            for (int fb = 0; fb < 2; ++fb)
+                av[fb] = *reinterpret_cast<const u32x4 *>(st + fa + 32u * fb * kGemmRow + fk[ks]);
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
-                bv[tb] = *reinterpret_cast<const u32x4 *>(st + fbt + 32u * tb * kGemmRow + 32u * ks);
+                bv[tb] = *reinterpret_cast<const u32x4 *>(st + fbt + 32u * tb * kGemmRow + fk[ks]);
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
+            for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb)
                     acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8_t, av[fb]), __builtin_bit_cast(bf16x8_t, bv[tb]), acc[fb][tb], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8_t, av[fb]), __builtin_bit_cast(bf16x8_t, bv[tb]),
+                        acc[fb][tb], 0, 0, 0);
         }
-        if (more) store_stage((kt + 1) & 1);
+    };
+    // registers -> LDS, barrier, the next stage's loads leave, multiply, barrier
+    load_stage(0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        store_stage(kt);
+        __syncthreads();
+        load_stage(kt + 1);
+        __builtin_amdgcn_sched_barrier(0);  // (the loads leave first: nothing is moved above them)
+        compute_stage(lds);
         __syncthreads();
     }
 
     // epilogue, one block of 32 tokens at a time
-    const uint32_t F0 = tileF + 128u * wm;
+    const uint32_t F0 = tileF + 64u * wm;
     const uint32_t h = ln >> 5;
     float *xch = reinterpret_cast<float *>(lds);  // (the stages are done with: the last barrier has passed)
-    const bool ragged = F0 + 128u > static_cast<uint32_t>(a.r);
+    const bool ragged = F0 + 64u > static_cast<uint32_t>(a.r);
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
         const int64_t t = tileT + 64 * wn + 32 * tb + (ln & 31u);
         const bool t_ok = t < a.T;
-        float y[4][16];
+        float y[2][16];
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb)
+        for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) y[fb][v] = round_via_bf16(acc[fb][tb][v]);
         const uint32_t tslot = 64u * wn + 32u * tb + (ln & 31u);
         const int64_t tc = t_ok ? t : 0;
-        if (G == 256) {
-            // (both waves of a group pass the barriers inside: one code path for everybody)
-            gemm_epilogue<G, true>(a, y, F0, tc, t_ok, h, xch, wm, tslot);
+        if (G > 64) {
+            // (the waves of a group pass the barriers inside together: the workgroup takes one path)
+            if (tileF + ROWS_A > static_cast<uint32_t>(a.r))
+                gemm_epilogue<G, WF, true>(a, y, F0, tc, t_ok, h, xch, wm, tslot, ROWS_B);
+            else
+                gemm_epilogue<G, WF, false>(a, y, F0, tc, t_ok, h, xch, wm, tslot, ROWS_B);
         } else if (ragged) {
-            gemm_epilogue<G, true>(a, y, F0, tc, t_ok, h, xch, wm, tslot);
+            gemm_epilogue<G, WF, true>(a, y, F0, tc, t_ok, h, xch, wm, tslot, ROWS_B);
         } else {
-            gemm_epilogue<G, false>(a, y, F0, tc, t_ok, h, xch, wm, tslot);
+            gemm_epilogue<G, WF, false>(a, y, F0, tc, t_ok, h, xch, wm, tslot, ROWS_B);
         }
     }
 }
@@ -348,22 +375,23 @@ int launch_gemm_encode(const tpq_layout *L, const uint16_t *X, int64_t T, int64_
     a.pitch_outl = L->pitch_outl;
     a.Ymsg = Ymsg;
     a.ldYm = ldYm;
-    const int64_t tiles_t = (T + kGemmTT - 1) / kGemmTT;
-    if (tiles_t > 65535) return TPQ_ERR_SHAPE;
-    const dim3 grid(static_cast<unsigned>((L->E + kGemmTF - 1) / kGemmTF), static_cast<unsigned>(tiles_t));
-    const size_t lds = 2 * kGemmStage;
     hipError_t e = hipSuccess;
-#define TPQ_GEMM(GG)                                                                                     \
-    case GG:                                                                                             \
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_encode<GG>),                      \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));      \
-        if (e == hipSuccess) launch_kernel(k_gemm_encode<GG>, grid, dim3(256), lds, s, a);               \
-        break;
+    // groups up to 128: workgroups of 2 x 2 waves (128 features x 128 tokens); groups of 256
+    // need 256 features in the workgroup: 4 x 1 waves (256 features x 64 tokens)
+#define TPQ_GEMM(GG, WF, WT)                                                                              \
+    case GG: {                                                                                            \
+        const int64_t tiles_t = (T + 64 * WT - 1) / (64 * WT);                                            \
+        if (tiles_t > 65535) return TPQ_ERR_SHAPE;                                                        \
+        const dim3 grid(static_cast<unsigned>((L->E + 64 * WF - 1) / (64 * WF)), static_cast<unsigned>(tiles_t)); \
+        const size_t lds = 64 * (WF + WT) * kGemmRow;                                                 \
+        launch_kernel(k_gemm_encode<GG, WF, WT>, grid, dim3(64 * WF * WT), lds, s, a);                    \
+        break;                                                                                            \
+    }
     switch (L->G) {
-        TPQ_GEMM(32)
-        TPQ_GEMM(64)
-        TPQ_GEMM(128)
-        TPQ_GEMM(256)
+        TPQ_GEMM(32, 2, 2)
+        TPQ_GEMM(64, 2, 2)
+        TPQ_GEMM(128, 2, 2)
+        TPQ_GEMM(256, 4, 1)
     default: return TPQ_ERR_UNSUPPORTED;
     }
 #undef TPQ_GEMM
