@@ -154,6 +154,8 @@ def section_large(tpq, wl, args):
     dev = "cuda"
     results = []
     for w in wl.large_variants():
+        if args.only and args.only not in w.name:
+            continue
         N, T, E = w.N, w.T, w.E
         L = tpq.layout_init(E, w.k, w.G)
         plan = tpq.plan_build(L, torch.from_numpy(idx_for(wl, w)).to(dev))
@@ -330,6 +332,8 @@ def section_gemm(tpq, wl, args):
     tpq.plan_check(L, plan)
     shapes = []
     for K in (1728, 640):
+        if args.only and args.only != str(K):
+            continue
         sets = []
         for s in range(4):
             X, Wt = wl.linear_inputs(T, K, E, idx, 100 + s, device=dev)
@@ -361,6 +365,8 @@ def section_gemm(tpq, wl, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--sections", default="llama,gemma,large,static,bits,fused,hop,gemm")
+    ap.add_argument("--only", default="", help="large: only the variants whose name contains this; gemm: only this K "
+                                               "(so that a kernel trace holds one shape per kernel)")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_configs.py: no GPU visible")

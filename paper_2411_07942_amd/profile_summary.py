@@ -78,6 +78,7 @@ def cmd_pmc(fetch_path, write_path, traffic_json=None):
           % (sum(fprobe) / len(fprobe), sum(wprobe) / len(wprobe), f_fac, w_fac))
     print("| kernel | grid | dispatches | FETCH_SIZE | WRITE_SIZE | read MB | written MB | total MB |\n|---|---|---|---|---|---|---|---|")
     totals = {}
+    counts = {}
     for key in sorted(set(fetch) | set(write)):
         f = fetch.get(key, [])
         w = write.get(key, [])
@@ -85,11 +86,14 @@ def cmd_pmc(fetch_path, write_path, traffic_json=None):
         wa = sum(w) / len(w) if w else 0.0
         rd, wr = fa * f_fac * 1024 / 1e6, wa * w_fac * 1024 / 1e6
         totals[key] = (rd + wr) * 1e6
+        counts[key] = max(len(f), len(w))
         print("| %s | %s | %d | %.0f | %.0f | %.1f | %.1f | %.1f |" % (key[0], key[1], max(len(f), len(w)), fa, wa, rd, wr, rd + wr))
     if traffic_json:
         def biggest(prefix):
-            c = [(int(k[1]), v) for k, v in totals.items() if k[0].startswith(prefix)]
-            return int(round(max(c)[1], -4)) if c else None
+            # the launch with the largest grid; among kernels with that grid (the accumulate modes
+            # of decode_reduce) the one dispatched most often, which is the mode bench.py times
+            c = [(int(k[1]), counts[k], v) for k, v in totals.items() if k[0].startswith(prefix)]
+            return int(round(max(c)[2], -4)) if c else None
         out = {"tpq_encode": biggest("tpq::k_encode_direct"), "tpq_decode_reduce": biggest("tpq::k_decode_pass"),
                "source": "rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, bytes per launch at the Llama-2-13B-shaped "
                          "prefill workload, scaled by the copy probe (paper_2411_07942_amd/profile_summary.py pmc)"}
