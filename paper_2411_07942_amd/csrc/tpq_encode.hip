@@ -121,8 +121,9 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     if constexpr (STATIC) {
         // the four waves of a workgroup take the same segment of four consecutive rows, and
         // share that segment's slice of the device's table through LDS (workgroup =
-        // (group of 4 rows, segment); the last group's waves past the last row only help
-        // with the table)
+        // (group of 4 rows, segment); the last group's waves past the last row help with the
+        // table and then work on the last row again without storing anything, so that all four
+        // waves reach the workgroup's one barrier at the same place)
         const uint32_t rg = segs == 1 ? blockIdx.x : __umulhi(blockIdx.x, a.segs_magic);
         seg = blockIdx.x - rg * segs;
         t = rg * 4u + wave;
@@ -237,10 +238,6 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
             const uint32_t j = threadIdx.x + 256u * i;
             if (j < static_cast<uint32_t>(P) * 128u) l_tab[(j & 1u) * (64u * P) + (j >> 1)] = tab_in[i];
         }
-        if (!active) {
-            __syncthreads();
-            return;
-        }
     }
 
     // A: windows -> slots (lanes that have one) and -> features (the others).  A lane's
@@ -305,7 +302,7 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
                     static_cast<const uint8_t *>(hin.outl[rank]) + static_cast<int64_t>(t) * a.pitch_outl)[s_lo + pc];
                 val = pack_bf16x2(bf16_bits_to_f32(in) + bf16_bits_to_f32(val), 0.0f) & 0xFFFFu;
             }
-            if (p < n_sel) outl[p] = static_cast<uint16_t>(val);
+            if (p < n_sel && active) outl[p] = static_cast<uint16_t>(val);
         }
     }
     for (uint32_t q0 = 0; q0 < n_ql; q0 += 64) {
@@ -606,6 +603,7 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
         for (int p = 0; p < P; ++p) {
             const uint32_t chunk = (pass0 + p) * 64u + ln;
             uint64_t wv = w64[p];
+            if (!active) continue;
             if (last_seg) {
                 const int n_valid = a.r - 8 * static_cast<int>(chunk);
                 if (n_valid < 8 && n_valid > 0) wv &= (1ull << (b * static_cast<uint32_t>(n_valid))) - 1ull;
@@ -656,12 +654,12 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
 #pragma unroll
         for (uint32_t u0 = 0; u0 < 16u * P; u0 += 64) {
             const uint32_t u = u0 + ln;
-            if (u < full)
+            if (u < full && active)
                 __builtin_nontemporal_store(reinterpret_cast<const u32x4 *>(l_codes)[u],
                                             reinterpret_cast<u32x4 *>(dst + 16u * u));
         }
         const uint32_t c = 4u * full + ln;
-        if (c < nc) __builtin_nontemporal_store(l_codes[c], reinterpret_cast<uint32_t *>(dst + 4u * c));
+        if (c < nc && active) __builtin_nontemporal_store(l_codes[c], reinterpret_cast<uint32_t *>(dst + 4u * c));
     }
 }
 
