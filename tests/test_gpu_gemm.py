@@ -32,9 +32,10 @@ def _ulp_bf16(x):
     return 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -126))) - 7)
 
 
-def _run(T, K, E, k, G, seed, integer=False, ld_pad=0, rows=None, want_y=True):
+def _run(T, K, E, k, G, seed, integer=False, ld_pad=0, rows=None, want_y=True, idx=None):
     rng = np.random.default_rng(seed)
-    idx = np.sort(rng.choice(E, k, replace=False)).astype(np.int32)
+    if idx is None:
+        idx = np.sort(rng.choice(E, k, replace=False)).astype(np.int32)
     X, Wt = wl.linear_inputs(T, K, E, idx, seed, device="cuda", integer=integer)
     if ld_pad:
         Xb = torch.zeros((T, K + ld_pad), dtype=torch.bfloat16, device="cuda")
@@ -125,6 +126,18 @@ def test_general_inputs(T, K, E, k, G):
 ])
 def test_exact_inputs_are_bit_exact_end_to_end(T, K, E, k, G):
     _run(T, K, E, k, G, seed=3 * T + K, integer=True)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(seed):
+    """Seeded random (E, k, G) with selected features in runs and at both ends of the row (the
+    generator of test_gpu_random_shapes), random T and K."""
+    from test_gpu_random_shapes import _shape
+    E, G, idx, _, _ = _shape(seed)
+    rng = np.random.default_rng(77 + seed)
+    T = int(rng.integers(1, 300))
+    K = 8 * int(rng.integers(1, 66))
+    _run(T, K, E, int(idx.size), G, seed=seed, integer=bool(seed % 4 == 3), idx=idx)
 
 
 def test_padded_rows_and_no_product_output():
