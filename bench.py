@@ -91,7 +91,7 @@ def event_us(tpq, calls, n):
     ev = [[new_event(), new_event()] for _ in range(n)]
     torch.cuda.synchronize()
     for i, e in enumerate(ev):
-        tpq.time_next_launch(e[0], e[1])
+        tpq.bench_time_next_launch(e[0], e[1])
         calls[i % len(calls)]()
     torch.cuda.synchronize()
     return float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e3
@@ -276,7 +276,7 @@ def main():
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / args.steps
     # kernel durations: a second pass over the same steps with HIP events attached to every
-    # launch's own dispatch (tpq_time_next_launch): each pair brackets one kernel on the stream it
+    # launch's own dispatch (tpq_bench_time_next_launch): each pair brackets one kernel on the stream it
     # runs on.  Kept out of the pass above because an attached launch costs some microseconds of
     # dispatch overhead, which would otherwise go into `value`.
     n_ev = min(args.steps, args.event_steps)
@@ -284,9 +284,9 @@ def main():
     torch.cuda.synchronize()
     for i, e in enumerate(ev):
         bufs = sets[i % len(sets)]
-        tpq.time_next_launch(e[0], e[1])
+        tpq.bench_time_next_launch(e[0], e[1])
         bufs[3]()
-        tpq.time_next_launch(e[2], e[3])
+        tpq.bench_time_next_launch(e[2], e[3])
         bufs[4]()
     torch.cuda.synchronize()
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))

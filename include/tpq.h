@@ -49,7 +49,7 @@
  *     aligned, leading dimensions / pitches as stated per argument.
  *   - The library never allocates, frees or retains device memory; all buffers
  *     belong to the caller.  There is no global state beyond two thread-local
- *     items (the last HIP error, a pending tpq_time_next_launch request); calls
+ *     items (the last HIP error, a pending tpq_bench_time_next_launch request); calls
  *     are re-entrant across streams.
  *   - Work is enqueued on the given HIP stream (a hipStream_t passed as void*,
  *     NULL = the default stream) and the call returns without synchronising,
@@ -121,14 +121,14 @@ int tpq_last_hip_error(void); /* hipError_t of the most recent TPQ_ERR_HIP on th
 
 /* Measurement aid (for benchmarks: no part of the method).  The next kernel that
  * tpq_encode, tpq_hop, tpq_encode_static, tpq_decode_reduce, tpq_decode_reduce_fused or
- * tpq_decode_reduce_static launches from the calling thread carries the two HIP events
+ * tpq_decode_reduce_static (or tpq_gemm_encode) launches from the calling thread carries the two HIP events
  * (hipEvent_t passed as void*, created by the caller with timing enabled) on its own
  * dispatch: afterwards hipEventElapsedTime(start, stop) is that kernel's duration on
  * the GPU, without the idle time that separately recorded events put around a launch.
  * One launch only (a call that splits its rows over several launches times the first);
  * a request stays pending, also across calls that fail their argument checks, until a
  * kernel is launched or both NULL cancel it. */
-int tpq_time_next_launch(void *start_event, void *stop_event);
+int tpq_bench_time_next_launch(void *start_event, void *stop_event);
 
 /* ---- plan: device tables derived from the static outlier index set -------
  * The selected features are fixed across sequences and devices (Sec. 3), so

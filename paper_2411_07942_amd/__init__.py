@@ -29,7 +29,7 @@ MAX_E = 32768
 
 EXPORTS = [
     "tpq_layout_init", "tpq_payload_bits", "tpq_wire_bits", "tpq_strerror", "tpq_last_hip_error",
-    "tpq_time_next_launch",
+    "tpq_bench_time_next_launch",
     "tpq_plan_bytes", "tpq_plan_build", "tpq_plan_check",
     "tpq_calibrate_workspace_bytes", "tpq_calibrate", "tpq_calibrate_fixed",
     "tpq_calibrate_finalize_workspace_bytes", "tpq_calibrate_finalize",
@@ -90,7 +90,7 @@ def _load():
     lib.tpq_calibrate_finalize_workspace_bytes.restype = sz
     lib.tpq_calibrate_finalize.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.tpq_encode.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, vp]
-    lib.tpq_time_next_launch.argtypes = [vp, vp]
+    lib.tpq_bench_time_next_launch.argtypes = [vp, vp]
     lib.tpq_hop.argtypes = [LP, vp, vp, i64, c_int, i64, vp, vp, vp, vp, c_int, vp, vp, vp, vp, vp]
     lib.tpq_gemm_weights.argtypes = [LP, vp, vp, i64, c_int, vp, vp]
     lib.tpq_gemm_encode.argtypes = [LP, vp, i64, i64, c_int, vp, vp, vp, vp, vp, vp, i64, vp]
@@ -273,17 +273,17 @@ def encode(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], msgs: Seque
     encode_call(L, plan, Y, msgs)(stream)
 
 
-def time_next_launch(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
+def bench_time_next_launch(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
     """Attach two timing events to the next encode / ring step / decode kernel launched from this
-    thread (tpq_time_next_launch).  The events must exist already (recorded once before), so that
+    thread (tpq_bench_time_next_launch).  The events must exist already (recorded once before), so that
     their handles can be passed; afterwards start.elapsed_time(stop) is the kernel's duration."""
     if start is None:
-        _check(_load().tpq_time_next_launch(None, None), "tpq_time_next_launch")
+        _check(_load().tpq_bench_time_next_launch(None, None), "tpq_bench_time_next_launch")
         return
     h0, h1 = start.cuda_event, stop.cuda_event
     if not h0 or not h1:
-        raise ValueError("time_next_launch: record each event once before handing it over")
-    _check(_load().tpq_time_next_launch(h0, h1), "tpq_time_next_launch")
+        raise ValueError("bench_time_next_launch: record each event once before handing it over")
+    _check(_load().tpq_bench_time_next_launch(h0, h1), "tpq_bench_time_next_launch")
 
 
 def hop_call(L: Layout, plan: torch.Tensor, Y: Sequence[torch.Tensor], in_msgs: Sequence[Message],

@@ -107,7 +107,7 @@ const char *tpq_strerror(int code)
 
 int tpq_last_hip_error(void) { return g_last_hip_error; }
 
-int tpq_time_next_launch(void *start_event, void *stop_event)
+int tpq_bench_time_next_launch(void *start_event, void *stop_event)
 {
     if ((start_event == nullptr) != (stop_event == nullptr)) return TPQ_ERR_NULL;
     g_launch_timer = LaunchTimer{static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};

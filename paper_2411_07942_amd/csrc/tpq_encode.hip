@@ -87,7 +87,8 @@ __device__ __forceinline__ uint64_t pack_codes(uint32_t lo, uint32_t hi)
 #define TPQ_HOP_OCC 5  // waves per SIMD of the ring step (15 more live registers than the encoder; 6: 2 % slower, 7: spills)
 #endif
 template <int P>
-struct DirectOcc {  // waves per SIMD the register budget is set for
+struct DirectOcc {  // waves per SIMD the register budget is set for (the static mode at other code
+                    // widths and 5 passes per wave needs two registers more than 8 waves leave: 7 there)
     static constexpr int value = 8;
 };
 
@@ -107,7 +108,7 @@ struct DirectOcc {  // waves per SIMD the register budget is set for
 // to bf16.  The received chunk's codes and its group's scale and zero are loaded with
 // the windows; the sums replace the features in registers before the group statistics.
 template <int LPG, int P, bool STATIC, bool GEN = false, bool HOP = false>
-__global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void k_encode_direct(
+__global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : (STATIC && GEN && P == 5) ? 7 : DirectOcc<P>::value) void k_encode_direct(
     EncodeArgs a, RankPtrs Yp, RankPtrs codesp, RankPtrs scalep, RankPtrs zerop, RankPtrs outlp, HopIn hin)
 {
     const uint32_t ln = threadIdx.x & 63u;
@@ -596,37 +597,83 @@ __global__ __launch_bounds__(256, HOP ? TPQ_HOP_OCC : DirectOcc<P>::value) void 
     }
     if constexpr (GEN) {
         // b bytes per chunk at byte chunk * b of the row (the row's pitch has room for whole
-        // chunks); a ragged last chunk's unused bits are zero
-        uint8_t *cb = reinterpret_cast<uint8_t *>(codes);
+        // chunks); a ragged last chunk's unused bits are zero.  As below, the segment's codes
+        // -- one contiguous piece of the row, 64 b bytes per pass -- are parked in the wave's
+        // slot area and leave as 128-bit stores; the last, partial 16 bytes go out byte by byte.
+        // (Measured at the Llama shape: 58 -> 50 us at 8 bits, 57 -> 53 at 6, 52 -> 49 at 3; at 2
+        // and 5 bits, and in the static mode, each lane's own narrow store is as fast or faster
+        // and stays.)
+        uint8_t *l_codes = slots;  // (the host gives the area 64 P b bytes at least)
         const uint32_t b = static_cast<uint32_t>(a.bits);
+        if (STATIC || b == 2 || b == 5) {
+            uint8_t *cb = reinterpret_cast<uint8_t *>(codes);
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const uint32_t chunk = (pass0 + p) * 64u + ln;
-            uint64_t wv = w64[p];
-            if (!active) continue;
-            if (last_seg) {
-                const int n_valid = a.r - 8 * static_cast<int>(chunk);
-                if (n_valid < 8 && n_valid > 0) wv &= (1ull << (b * static_cast<uint32_t>(n_valid))) - 1ull;
-                if (chunk >= static_cast<uint32_t>(a.chunks)) continue;
+            for (int p = 0; p < P; ++p) {
+                const uint32_t chunk = (pass0 + p) * 64u + ln;
+                uint64_t wv = w64[p];
+                if (!active) continue;
+                if (last_seg) {
+                    const int n_valid = a.r - 8 * static_cast<int>(chunk);
+                    if (n_valid < 8 && n_valid > 0) wv &= (1ull << (b * static_cast<uint32_t>(n_valid))) - 1ull;
+                    if (chunk >= static_cast<uint32_t>(a.chunks)) continue;
+                }
+                uint8_t *dst = cb + chunk * b;
+                const uint32_t lo = static_cast<uint32_t>(wv), hi = static_cast<uint32_t>(wv >> 32);
+                switch (b) {
+                case 2: *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(lo); break;
+                case 3:
+                    *reinterpret_cast<u16_a1 *>(dst) = static_cast<uint16_t>(lo);
+                    dst[2] = static_cast<uint8_t>(lo >> 16);
+                    break;
+                case 5:
+                    *reinterpret_cast<u32_a1 *>(dst) = lo;
+                    dst[4] = static_cast<uint8_t>(hi);
+                    break;
+                case 6:
+                    *reinterpret_cast<u32_a2 *>(dst) = lo;
+                    *reinterpret_cast<uint16_t *>(dst + 4) = static_cast<uint16_t>(hi);
+                    break;
+                default: *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi); break;
+                }
             }
-            uint8_t *dst = cb + chunk * b;
-            const uint32_t lo = static_cast<uint32_t>(wv), hi = static_cast<uint32_t>(wv >> 32);
-            switch (b) {
-            case 2: *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(lo); break;
-            case 3:
-                *reinterpret_cast<u16_a1 *>(dst) = static_cast<uint16_t>(lo);
-                dst[2] = static_cast<uint8_t>(lo >> 16);
-                break;
-            case 5:
-                *reinterpret_cast<u32_a1 *>(dst) = lo;
-                dst[4] = static_cast<uint8_t>(hi);
-                break;
-            case 6:
-                *reinterpret_cast<u32_a2 *>(dst) = lo;
-                *reinterpret_cast<uint16_t *>(dst + 4) = static_cast<uint16_t>(hi);
-                break;
-            default: *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi); break;
+            return;
+        }
+        if constexpr (!STATIC) {
+    #pragma unroll
+            for (int p = 0; p < P; ++p) {
+                uint64_t wv = w64[p];
+                if (last_seg) {
+                    const int n_valid = a.r - 8 * static_cast<int>((pass0 + p) * 64u + ln);
+                    if (n_valid < 8 && n_valid > 0) wv &= (1ull << (b * static_cast<uint32_t>(n_valid))) - 1ull;
+                }
+                uint8_t *d = l_codes + (static_cast<uint32_t>(p) * 64u + ln) * b;
+                const uint32_t lo = static_cast<uint32_t>(wv), hi = static_cast<uint32_t>(wv >> 32);
+                switch (b) {
+                case 3:
+                    d[0] = static_cast<uint8_t>(lo);
+                    d[1] = static_cast<uint8_t>(lo >> 8);
+                    d[2] = static_cast<uint8_t>(lo >> 16);
+                    break;
+                case 6:
+                    *reinterpret_cast<uint16_t *>(d) = static_cast<uint16_t>(lo);
+                    *reinterpret_cast<uint16_t *>(d + 2) = static_cast<uint16_t>(lo >> 16);
+                    *reinterpret_cast<uint16_t *>(d + 4) = static_cast<uint16_t>(hi);
+                    break;
+                default: *reinterpret_cast<uint2 *>(d) = make_uint2(lo, hi); break;
+                }
             }
+            wave_lds_fence();
+            const uint32_t nc = last_seg ? static_cast<uint32_t>(a.chunks) - pass0 * 64u : 64u * P;  // chunks to store
+            const uint32_t nbytes = nc * b, full = nbytes >> 4;
+            uint8_t *dst = reinterpret_cast<uint8_t *>(codes) + 64u * b * pass0;
+            for (uint32_t u0 = 0; u0 < full; u0 += 64) {
+                const uint32_t u = u0 + ln;
+                if (u < full && active)
+                    __builtin_nontemporal_store(reinterpret_cast<const u32x4 *>(l_codes)[u],
+                                                reinterpret_cast<u32x4 *>(dst + 16u * u));
+            }
+            const uint32_t c = 16u * full + ln;
+            if (c < nbytes && active) dst[c] = l_codes[c];
         }
         return;
     }
@@ -709,6 +756,7 @@ static hipError_t launch_direct(const EncodeArgs &a_in, const RankPtrs &Y_in, co
     if (a.patch_slots > a.dslots) a.patch_slots = a.dslots;
     if (a.patch_slots > 64 * P) a.patch_slots = 64 * P;
     if (a.patch_slots < 8 * P) a.patch_slots = 8 * P;  // (the codes pass through the same area: 256 P bytes)
+    if (a.bits != 4 && a.patch_slots < 2 * P * a.bits) a.patch_slots = 2 * P * a.bits;  // (other widths: 64 P b bytes)
     const bool is_static = a.inv_c != nullptr;
     const bool is_gen = a.bits != 4;
     // per wave: slots (+ the groups' scale / zero pairs); static mode: + the workgroup's table slice

@@ -262,7 +262,7 @@ int check_layout(const tpq_layout *L);  // TPQ_OK or an error code
 void set_last_hip_error(hipError_t e);
 int hip_result(hipError_t e);  // TPQ_OK, or records e and returns TPQ_ERR_HIP
 
-// One-shot timing request of the calling thread (tpq_time_next_launch): the next encode /
+// One-shot timing request of the calling thread (tpq_bench_time_next_launch): the next encode /
 // ring step / decode kernel is launched with these two events attached to its dispatch.
 struct LaunchTimer {
     hipEvent_t start, stop;

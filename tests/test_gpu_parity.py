@@ -504,7 +504,7 @@ def test_hip_graph_replays_match_eager():
 
 
 def test_timing_events_on_a_launch():
-    """tpq_time_next_launch: the events bracket the next kernel only; results are unchanged."""
+    """tpq_bench_time_next_launch: the events bracket the next kernel only; results are unchanged."""
     w = wl.TINY
     Ys = wl.partial_sums(w, device="cuda")
     idx = idx_for(w)
@@ -517,9 +517,9 @@ def test_timing_events_on_a_launch():
     torch.cuda.synchronize()
     timed = [tpq.Message(L, w.T, "cuda", fill=CANARY) for _ in Ys]
     out = torch.empty((w.T, w.E), dtype=torch.bfloat16, device="cuda")
-    tpq.time_next_launch(ev[0], ev[1])
+    tpq.bench_time_next_launch(ev[0], ev[1])
     tpq.encode(L, plan, Ys, timed)
-    tpq.time_next_launch(ev[2], ev[3])
+    tpq.bench_time_next_launch(ev[2], ev[3])
     tpq.decode_reduce(L, plan, timed, out, tpq.ACC_BF16)
     tpq.decode_reduce(L, plan, timed, out, tpq.ACC_BF16)   # no request pending: a plain launch
     torch.cuda.synchronize()
@@ -528,7 +528,7 @@ def test_timing_events_on_a_launch():
             assert torch.equal(getattr(a, name), getattr(b, name))
     assert 0.0 < ev[0].elapsed_time(ev[1]) < 50.0
     assert 0.0 < ev[2].elapsed_time(ev[3]) < 50.0
-    tpq.time_next_launch(ev[0], ev[1])
-    tpq.time_next_launch(None, None)                       # cancelled
+    tpq.bench_time_next_launch(ev[0], ev[1])
+    tpq.bench_time_next_launch(None, None)                       # cancelled
     lib = tpq._load()
-    assert lib.tpq_time_next_launch(ev[0].cuda_event, None) == tpq.ERR_NULL
+    assert lib.tpq_bench_time_next_launch(ev[0].cuda_event, None) == tpq.ERR_NULL
