@@ -56,6 +56,37 @@ int check_layout(const tpq_layout *L)
 
 using namespace tpq;
 
+// The argument blocks' common part: the layout's numbers, the plan, the launch's extent.
+static EncodeArgs encode_args(const tpq_layout *L, const void *plan, int n_ranks, int64_t T, int64_t ldY)
+{
+    EncodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldY = ldY;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    return a;
+}
+
+static DecodeArgs decode_args(const tpq_layout *L, const void *plan, int n_ranks, int64_t T, void *out,
+                              int64_t ldOut)
+{
+    DecodeArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = static_cast<const uint8_t *>(plan);
+    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
+    a.chunks = chunks_of(L->r);
+    a.chunks_padded = chunks_padded_of(L->r);
+    a.n_ranks = n_ranks;
+    a.T = T; a.ldOut = ldOut;
+    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    a.out = out;
+    return a;
+}
+
 extern "C" {
 
 int tpq_layout_init(tpq_layout *L, int E, int k, int G, int bits)
@@ -259,15 +290,7 @@ int tpq_encode(const tpq_layout *L, const void *plan, const uint16_t *const *Y, 
     if ((rc = gather_ptrs(pz, reinterpret_cast<const void *const *>(zero), n_ranks, quant))) return rc;
     if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
     if (T == 0) return TPQ_OK;
-    EncodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldY = ldY;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    EncodeArgs a = encode_args(L, plan, n_ranks, T, ldY);
     a.bits = L->bits;
     a.qmax = static_cast<float>((1 << L->bits) - 1);
     return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream));
@@ -344,15 +367,7 @@ int tpq_hop(const tpq_layout *L, const void *plan, const uint16_t *const *Y, int
         hin.zero[i] = iz.p[i];
         hin.outl[i] = io.p[i];
     }
-    EncodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldY = ldY;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    EncodeArgs a = encode_args(L, plan, n_ranks, T, ldY);
     a.bits = L->bits;
     a.qmax = 15.0f;
     return launch_encode(a, pY, pc, ps, pz, po, static_cast<hipStream_t>(stream), &hin);
@@ -379,16 +394,7 @@ int tpq_decode_reduce(const tpq_layout *L, const void *plan, int n_ranks, int64_
     if ((rc = gather_ptrs(pz, reinterpret_cast<const void *const *>(zero), n_ranks, quant))) return rc;
     if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
     if (T == 0) return TPQ_OK;
-    DecodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldOut = ldOut;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
-    a.out = out;
+    DecodeArgs a = decode_args(L, plan, n_ranks, T, out, ldOut);
     a.bits = L->bits;
     return launch_decode(a, pc, ps, pz, po, accum, out_dtype, static_cast<hipStream_t>(stream));
 }
@@ -418,16 +424,7 @@ int tpq_decode_reduce_fused(const tpq_layout *L, const void *plan, int n_ranks, 
     if ((rc = gather_ptrs(pz, reinterpret_cast<const void *const *>(zero), n_ranks, quant))) return rc;
     if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
     if (T == 0) return TPQ_OK;
-    DecodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldOut = ldOut;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
-    a.out = out;
+    DecodeArgs a = decode_args(L, plan, n_ranks, T, out, ldOut);
     a.bits = 4;
     a.addend = reinterpret_cast<const uint8_t *>(addend);
     a.ldAdd = ldAdd;
@@ -475,15 +472,7 @@ int tpq_encode_static(const tpq_layout *L, const void *plan, const uint16_t *con
     if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
     if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
     if (T == 0) return TPQ_OK;
-    EncodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldY = ldY;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
+    EncodeArgs a = encode_args(L, plan, n_ranks, T, ldY);
     a.inv_c = inv;
     a.static_stride = 8 * a.chunks_padded;
     a.bits = L->bits;
@@ -513,16 +502,7 @@ int tpq_decode_reduce_static(const tpq_layout *L, const void *plan, int n_ranks,
     if ((rc = gather_ptrs(pc, reinterpret_cast<const void *const *>(codes), n_ranks, quant))) return rc;
     if ((rc = gather_ptrs(po, reinterpret_cast<const void *const *>(outl), n_ranks, keep))) return rc;
     if (T == 0) return TPQ_OK;
-    DecodeArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = static_cast<const uint8_t *>(plan);
-    a.E = L->E; a.k = L->k; a.G = L->G; a.r = L->r; a.ng = L->ng;
-    a.chunks = chunks_of(L->r);
-    a.chunks_padded = chunks_padded_of(L->r);
-    a.n_ranks = n_ranks;
-    a.T = T; a.ldOut = ldOut;
-    a.pitch_codes = L->pitch_codes; a.pitch_meta = L->pitch_meta; a.pitch_outl = L->pitch_outl;
-    a.out = out;
+    DecodeArgs a = decode_args(L, plan, n_ranks, T, out, ldOut);
     a.step_c = quant ? step : nullptr;
     a.static_stride = 8 * a.chunks_padded;
     a.bits = L->bits;
