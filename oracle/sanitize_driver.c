@@ -8,7 +8,8 @@
  * input : int32 N, T, E, k, G; int32 idx[k]; uint16 Y[N][T][E]
  * output: per device outl, codes, scale, zero; the reduced sums (fp32 chain as fp32, bf16 chain
  *         as bf16); the same at 3 bits; calibration state after N sequences, ranges and indices;
- *         static parameters, static messages and their reduced sum; the fused epilogue.
+ *         static parameters, static messages and their reduced sum; the fused epilogue; the linear
+ *         layer on two of the tensors.
  */
 #include "tpq_oracle.c"
 
@@ -127,6 +128,17 @@ int main(int argc, char **argv)
         put(out, s16, 2u * (size_t)T * E);
         for (int i = 0; i < N; ++i) { free(outl[i]); free(codes[i]); }
         free(outl); free(codes); free(s16);
+    }
+    /* the linear layer: device 0's tensor as the activations [T][E], device 1's first min(T, 7)
+     * rows as a weight slice of that many output features (K = E) */
+    if (N >= 2) {
+        const int Eo = T < 7 ? T : 7;
+        uint16_t *Yl = malloc(2u * (size_t)T * (size_t)Eo);
+        double *mag = malloc(8u * (size_t)T * (size_t)Eo);
+        if (orc_linear(Y, T, E, E, Y + (size_t)T * E, Eo, E, Yl, Eo, mag, 1)) return 12;
+        put(out, Yl, 2u * (size_t)T * (size_t)Eo);
+        put(out, mag, 8u * (size_t)T * (size_t)Eo);
+        free(Yl); free(mag);
     }
     free(step); free(inv); free(R); free(Rbar); free(is); free(ir); free(m); free(M); free(Y); free(idx);
     fclose(out);

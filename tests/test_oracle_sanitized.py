@@ -56,6 +56,9 @@ def _expected(Ys, idx, E, G):
     for mg in smsgs:
         parts += [mg.outl, mg.codes]
     parts.append(oracle.decode_reduce_static(smsgs, idx, step, oracle.ACC_BF16, out_fp32=False))
+    if N >= 2:   # the linear layer: device 0's tensor times the first rows of device 1's
+        Yl, mag = oracle.linear(Ys[0], Ys[1][: min(T, 7)], with_magnitude=True)
+        parts += [Yl, mag]
     return b"".join(np.ascontiguousarray(p).tobytes() for p in parts)
 
 
