@@ -85,3 +85,21 @@ def test_random_shape(seed):
     fused_case(E, G, Ys, idx, addend if seed % 4 != 3 else None, bias if seed % 2 else None)
     own = _data(E, T, N, idx, seed + 100)
     hop_case(E, G, Ys, own, idx)
+
+
+@pytest.mark.parametrize("E,G,cols,bits", [
+    (5120, 128, [5 + 31 * i for i in range(80)], 3),
+    (8192, 64, [3 + 11 * i for i in range(341)], 8),
+    (8192, 128, [3 + 11 * i for i in range(300)] + list(range(3300, 3341)), 6),
+], ids=["llama_width_first_segment", "large_width_two_segments", "large_width_with_run"])
+def test_crowded_segments_in_every_mode(E, G, cols, bits):
+    """Selected features crowded into part of the row, so that a segment has more cut chunks than
+    the encoder's LDS area holds slots for: the static mode, another code width and the ring step
+    run the same encoder code in kernels of their own."""
+    T, N = 5, 2
+    idx = np.array(sorted(set(cols)), np.int32)
+    Ys = _data(E, T, N, idx, 900 + len(cols))
+    m, M = _ranges_from(Ys)
+    _static_case(E, G, Ys, idx, m, M)
+    bits_case(E, G, bits, Ys, idx)
+    hop_case(E, G, Ys, _data(E, T, N, idx, 901 + len(cols)), idx)
