@@ -14,7 +14,7 @@ import torch
 import oracle
 import paper_2411_07942_amd as tpq
 import workloads as wl
-from gpu_common import (CANARY, assert_message_equal, check_pad_bytes, gpu_decode, gpu_encode,
+from gpu_common import (bits_to_f32, CANARY, assert_message_equal, check_pad_bytes, gpu_decode, gpu_encode,
                         gpu_plan, idx_for, sum_tolerance_fraction, sum_tolerance_ok)
 from refmath import compaction
 
@@ -56,6 +56,17 @@ def _codec_case(w, Ys_dev, idx, rows=None, modes=((tpq.ACC_FP32, False), (tpq.AC
             # ... and evaluated as the fp32 chain, so identical to that
             want = oracle.decode_reduce(refs, idx, w.E, w.G, tpq.ACC_FP32, out_fp32=out_fp32, threads=8)
             assert np.array_equal(got, want), "fast mode differs from the fp32 chain"
+            # ... which puts it within half a bf16 ulp (one rounding) of the exact sum of the dequantised
+            # messages, up to the fp32 additions' own rounding (n_terms * 2^-24 of the magnitudes)
+            exact = np.zeros(got.shape, np.float64)
+            mag = np.zeros(got.shape, np.float64)
+            for mg in refs:
+                x = oracle.dequantize(mg, idx, w.E, w.G).astype(np.float64)
+                exact += x
+                mag += np.abs(x)
+            g64 = (got if out_fp32 else bits_to_f32(got)).astype(np.float64)
+            half_ulp = 0.0 if out_fp32 else 2.0 ** (np.floor(np.log2(np.maximum(np.abs(exact), 2.0 ** -126))) - 8)
+            assert np.all(np.abs(g64 - exact) <= half_ulp * (1 + 2.0 ** -7) + n_terms * 2.0 ** -24 * mag + 1e-37)
             continue
         want = oracle.decode_reduce(refs, idx, w.E, w.G, accum, out_fp32=out_fp32, threads=8)
         rel = 1e-2 if accum == tpq.ACC_BF16 else 1e-5
