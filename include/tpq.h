@@ -12,7 +12,10 @@
  *     Fig. 2 -- the k selected features of every row are sent verbatim in
  *     BF16, the other r = E-k features as bit-packed 4-bit codes;
  *   - tpq_decode_reduce: the decompression D^(i) of all N devices' messages
- *     and their sum (Sec. 2; Fig. 2 caption), features back in original order.
+ *     and their sum (Sec. 2; Fig. 2 caption), features back in original order;
+ *   - further down: the static symmetric mode of Sec. 3, other code widths (Sec. 4), the
+ *     block's epilogue inside decode_reduce, a ring step (Sec. 5), and the device's linear
+ *     layer f^(i)(x^(i)) = x^(i) W^(i) of Sec. 2 with the compression in its epilogue.
  *
  * Quantiser (the workload definition's group-wise asymmetric form): the r
  * non-selected features of a row, taken in ascending feature order
@@ -49,8 +52,10 @@
  *     aligned, leading dimensions / pitches as stated per argument.
  *   - The library never allocates, frees or retains device memory; all buffers
  *     belong to the caller.  There is no global state beyond two thread-local
- *     items (the last HIP error, a pending tpq_bench_time_next_launch request); calls
- *     are re-entrant across streams.
+ *     items (the last HIP error, a pending tpq_bench_time_next_launch request), the
+ *     number of compute units of each device (looked up once), and the static device
+ *     array of tpq_calibrate_fixed, the one call that brings its own scratch; calls
+ *     are re-entrant across streams (tpq_calibrate_fixed: see there).
  *   - Work is enqueued on the given HIP stream (a hipStream_t passed as void*,
  *     NULL = the default stream) and the call returns without synchronising,
  *     except tpq_plan_check.
